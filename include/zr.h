@@ -1,0 +1,150 @@
+/*
+ * zr.h - C ABI of the MI355X (gfx950) library for one tensor-parallel task's
+ *        resized shard GEMMs (ZERO-resizing, arXiv 2401.11469, Sec. 3).
+ *
+ * A straggling task prunes a priority-selected subset of one axis of its
+ * weight shard for one step, multiplies what is left (forward, dX, dW), and
+ * recovers the normal shape of every output by imputing the missing slices
+ * (Sec. 3.1 "Overview Resizing Design", "Consistency Constraint").
+ *
+ * Notation.  M = tokens (bs*sql).  X[M x K] activations, W[K x N] weight shard
+ * (in-features x out-features), Y[M x N] = X W, dY[M x N], dX[M x K] = dY W^T,
+ * dW[K x N] = X^T dY.  The paper stores weight as [out, in]; its "columns of
+ * input and weight" are axis K here.
+ *
+ * General conventions
+ *  - Every tensor / index pointer is a DEVICE pointer owned by the caller.  The
+ *    library allocates nothing, frees nothing and keeps no state between calls.
+ *  - Tensors are row-major; leading dimensions (ld*) are in ELEMENTS and must be
+ *    >= the row length.  bf16 tensors whose base is 16-byte aligned and whose
+ *    ld is a multiple of 8 (fp32: 4) take the vectorised paths; anything else is
+ *    still computed correctly on an element-wise path.
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*;
+ *    NULL = the default stream) and never synchronises, except
+ *    zr_validate_keep_idx, which is a debugging aid.
+ *  - Errors are return codes; no call aborts or throws.  On any error no kernel
+ *    is launched and the outputs are untouched.
+ *  - keep_idx is the kept index set: int32, strictly ascending, unique, within
+ *    [0, n) of the pruned axis.  It plays the role of the paper's lineage
+ *    tuple: the same list is shared by input and weight (Sec. 3.2) and reused
+ *    from forward to backward.  A list violating this gives undefined OUTPUT
+ *    VALUES but never an out-of-range access: indices are clamped into range.
+ *  - Accumulation is always fp32; outputs have the input dtype.  Kept
+ *    contributions are not rescaled (outputs just miss the pruned partial
+ *    products, Sec. 3.2 first paragraph).
+ */
+#ifndef ZR_H
+#define ZR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZR_OK = 0,
+    ZR_ERR_NULL = 1,      /* a required pointer is NULL */
+    ZR_ERR_SHAPE = 2,     /* a size is negative/zero where it may not be, or ld < row length */
+    ZR_ERR_RATIO = 3,     /* ratio outside [0,1) or it leaves no kept index */
+    ZR_ERR_INDEX = 4,     /* n_keep outside [1, n] (or, from the validator, a bad list) */
+    ZR_ERR_DTYPE = 5,
+    ZR_ERR_MODE = 6,
+    ZR_ERR_POLICY = 7,    /* unknown policy, or SAME without the previous tensor */
+    ZR_ERR_LIMIT = 8,     /* size beyond what the kernels index with int32 */
+    ZR_ERR_HIP = 9        /* a HIP runtime call failed (launch error) */
+} zr_status;
+
+typedef enum { ZR_F32 = 0, ZR_BF16 = 1 } zr_dtype;
+
+/* Which axis of W[K x N] keep_idx indexes.
+ *  ZR_DROP_K: the contraction axis (the paper's worked example, and the reading
+ *             used for row-parallel shards): Y keeps its shape and misses
+ *             partial products; dX loses columns, dW loses rows -> imputed.
+ *  ZR_DROP_N: the output-feature axis (the dual case, used for column-parallel
+ *             shards): Y and dW lose columns -> imputed; dX keeps its shape. */
+typedef enum { ZR_DROP_N = 0, ZR_DROP_K = 1 } zr_mode;
+
+/* Imputation policies of Sec. 3.1 ("what value should be imputed"). */
+typedef enum {
+    ZR_IMPUTE_ZERO = 0,     /* +0.0 (the paper's final choice) */
+    ZR_IMPUTE_AVERAGE = 1,  /* element-wise mean of the kept slices of this result */
+    ZR_IMPUTE_SAME = 2      /* value of the previous iteration's tensor at that position */
+} zr_policy;
+
+const char* zr_status_string(int status);
+
+/* Kept count for a pruned axis of length n at pruning ratio gamma
+ * (Algorithm 1: L_pri = L*(1-gamma)), rounded half-up in IEEE double:
+ * floor((1-ratio)*n + 0.5).  Pure host function.  Returns -1 if n < 0 or ratio is
+ * outside [0,1) (NaN included). */
+int64_t zr_keep_count(int64_t n, double ratio);
+
+/* Priority selection (Algorithm 1: top-L_pri select, then ascending sort).
+ *  scores   [batch x n] fp32, row b at scores + b*n: importance of each index
+ *           (larger = kept first).  NaN ranks lowest, -0.0 == +0.0, ties keep the
+ *           lower index.
+ *  keep_idx [batch x ld_idx] int32 out: row b receives the n' = zr_keep_count(n,
+ *           ratio) kept indices, ascending.  ld_idx >= n'.
+ *  drop_idx [batch x ld_idx] int32 out or NULL: the n - n' pruned indices,
+ *           ascending (the set P of the lineage tuple).  ld_idx >= n - n' too.
+ *  One launch; one workgroup per score vector.  n <= 2^24.
+ *  Errors: NULL, SHAPE (n < 1, batch < 1, ld_idx too small), RATIO, LIMIT. */
+int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio,
+                     int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, void* stream);
+
+/* Forward of the resized linear layer (Sec. 3.1, forward paragraph).
+ *  DROP_K: Y = X[:,S] W[S,:]            (full shape, nothing to impute)
+ *  DROP_N: Y[:,S] = X W[:,S];  Y[:,P] imputed by `policy`
+ *  X [M x K] ldx, W [K x N] ldw, Y [M x N] ldy (out, every element written).
+ *  keep_idx[n_keep] indexes K (DROP_K) or N (DROP_N).
+ *  prev_Y: previous iteration's Y [M x N] with leading dimension ldy, needed for
+ *  ZR_IMPUTE_SAME in DROP_N only (may alias Y: dropped positions then stay as
+ *  they are); ignored otherwise.
+ *  Launches: 1 for ZERO; 2 for AVERAGE / SAME (GEMM, then the imputation pass).
+ *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE, POLICY, LIMIT, HIP. */
+int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
+                          void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
+                          const int32_t* keep_idx, int32_t n_keep,
+                          int mode, int dtype, int policy, const void* prev_Y, void* stream);
+
+/* Backward of the resized linear layer (Sec. 3.1, backward paragraph; the
+ * upstream gradient is never pruned in the paper's DROP_K case).
+ *  DROP_K: dX[:,S] = dY W[S,:]^T, dX[:,P] imputed;  dW[S,:] = X[:,S]^T dY, dW[P,:] imputed
+ *  DROP_N: dX = dY[:,S] W[:,S]^T (full shape);      dW[:,S] = X^T dY[:,S], dW[:,P] imputed
+ *  dX [M x K] lddx and dW [K x N] lddw are outputs; either may be NULL to skip
+ *  that product.  prev_dX / prev_dW (same shapes and leading dimensions as dX /
+ *  dW) are read for ZR_IMPUTE_SAME only.
+ *  Errors as for the forward call. */
+int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
+                          const void* dY, int64_t lddy,
+                          void* dX, int64_t lddx, void* dW, int64_t lddw,
+                          int32_t M, int32_t K, int32_t N,
+                          const int32_t* keep_idx, int32_t n_keep,
+                          int mode, int dtype, int policy,
+                          const void* prev_dX, const void* prev_dW, void* stream);
+
+/* Stand-alone recovery/imputation (Sec. 3.1, "Our solution is to add missing
+ * dimensions" and the three policies): fills every slice of out[rows x cols]
+ * that is NOT in keep_idx along `axis` (0: keep_idx indexes rows, 1: columns);
+ * kept slices are left as they are.
+ *  ZERO: +0.0.  SAME: prev[same position] (prev has out's shape and ld; prev ==
+ *  out is allowed and is a no-op).  AVERAGE: mean, in fp32, of the kept slices'
+ *  stored values (axis 1: per-row mean over kept columns; axis 0: per-column
+ *  mean over kept rows), rounded to the tensor's dtype.
+ *  Errors: NULL, SHAPE, INDEX, DTYPE, POLICY, LIMIT, HIP. */
+int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
+              const int32_t* keep_idx, int32_t n_keep, int policy, const void* prev,
+              int dtype, void* stream);
+
+/* Debugging aid: checks on the device that keep_idx[n_keep] is strictly
+ * ascending and within [0, n).  SYNCHRONISES `stream`.  `flag` is a caller-owned
+ * device int32 used as scratch.  Returns ZR_OK or ZR_ERR_INDEX. */
+int zr_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t n,
+                         int32_t* flag, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZR_H */

@@ -1,0 +1,212 @@
+// C ABI of libzr: argument validation and the mapping of the six resized
+// products (paper Sec. 3.1) onto the canonical gather-fused GEMM.
+#include <cmath>
+
+#include "zr_common.h"
+
+using namespace zr;
+
+namespace {
+
+const int64_t kMaxDim = 0x7fffffff;
+
+bool valid_dtype(int dt) { return dt == ZR_F32 || dt == ZR_BF16; }
+bool valid_mode(int m) { return m == ZR_DROP_N || m == ZR_DROP_K; }
+bool valid_policy(int p) { return p == ZR_IMPUTE_ZERO || p == ZR_IMPUTE_AVERAGE || p == ZR_IMPUTE_SAME; }
+
+int check_common(int32_t M, int32_t K, int32_t N, const int32_t* keep_idx, int32_t n_keep,
+                 int mode, int dtype, int policy)
+{
+    if (!valid_dtype(dtype)) return ZR_ERR_DTYPE;
+    if (!valid_mode(mode)) return ZR_ERR_MODE;
+    if (!valid_policy(policy)) return ZR_ERR_POLICY;
+    if (M < 1 || K < 1 || N < 1) return ZR_ERR_SHAPE;
+    if (!keep_idx) return ZR_ERR_NULL;
+    const int32_t n = mode == ZR_DROP_N ? N : K;
+    if (n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
+    return ZR_OK;
+}
+
+Operand operand(const void* base, int64_t ld, bool c_contig, const int32_t* map_strided,
+                const int32_t* map_contig, int n_strided, int n_contig)
+{
+    Operand o;
+    o.base = base; o.ld = ld; o.c_contig = c_contig;
+    o.map_strided = map_strided; o.map_contig = map_contig;
+    o.n_strided = n_strided; o.n_contig = n_contig;
+    return o;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* zr_status_string(int status)
+{
+    switch (status) {
+        case ZR_OK: return "ok";
+        case ZR_ERR_NULL: return "a required pointer is NULL";
+        case ZR_ERR_SHAPE: return "bad shape or leading dimension";
+        case ZR_ERR_RATIO: return "ratio outside [0,1) or no index kept";
+        case ZR_ERR_INDEX: return "bad kept count or kept-index list";
+        case ZR_ERR_DTYPE: return "unknown dtype";
+        case ZR_ERR_MODE: return "unknown mode";
+        case ZR_ERR_POLICY: return "unknown policy or missing previous tensor";
+        case ZR_ERR_LIMIT: return "size beyond the supported limit";
+        case ZR_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int64_t zr_keep_count(int64_t n, double ratio)
+{
+    if (n < 0 || !(ratio >= 0.0) || !(ratio < 1.0)) return -1;
+    // floor((1 - ratio) * n + 0.5) with every operation rounded to double
+    // (no fused multiply-add: the product is stored before the addition)
+    volatile double kept = (1.0 - ratio) * (double)n;
+    volatile double shifted = kept + 0.5;
+    return (int64_t)std::floor(shifted);
+}
+
+int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio,
+                     int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, void* stream)
+{
+    if (!scores || !keep_idx) return ZR_ERR_NULL;
+    if (n < 1 || batch < 1) return ZR_ERR_SHAPE;
+    if (n > (1 << 24)) return ZR_ERR_LIMIT;
+    const int64_t n_keep = zr_keep_count(n, ratio);
+    if (n_keep < 1) return ZR_ERR_RATIO;
+    if (ld_idx < n_keep || (drop_idx && ld_idx < n - n_keep)) return ZR_ERR_SHAPE;
+    return launch_select(scores, n, batch, (int)n_keep, keep_idx, drop_idx, ld_idx, (hipStream_t)stream);
+}
+
+int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
+                          void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
+                          const int32_t* keep_idx, int32_t n_keep,
+                          int mode, int dtype, int policy, const void* prev_Y, void* stream)
+{
+    if (!X || !W || !Y) return ZR_ERR_NULL;
+    int st = check_common(M, K, N, keep_idx, n_keep, mode, dtype, policy);
+    if (st != ZR_OK) return st;
+    if (ldx < K || ldw < N || ldy < N) return ZR_ERR_SHAPE;
+    const bool full = n_keep == (mode == ZR_DROP_N ? N : K);   // ascending + unique + full count = identity
+    const bool needs_prev = mode == ZR_DROP_N && policy == ZR_IMPUTE_SAME && !full;
+    if (needs_prev && !prev_Y) return ZR_ERR_POLICY;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t* S = full ? nullptr : keep_idx;
+
+    GemmDesc d;
+    d.dtype = dtype;
+    d.out = Y; d.ldo = ldy; d.keep_idx = S; d.I = M;
+    if (mode == ZR_DROP_K) {
+        // Y[m,j] = sum_{c<n'} X[m,S[c]] * W[S[c],j]
+        d.A = operand(X, ldx, true, nullptr, S, M, K);
+        d.B = operand(W, ldw, false, S, nullptr, K, N);
+        d.J = N; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = N;
+        return launch_gemm(d, s);
+    }
+    // Y[m,S[j]] = sum_k X[m,k] * W[k,S[j]], dropped columns imputed
+    d.A = operand(X, ldx, true, nullptr, nullptr, M, K);
+    d.B = operand(W, ldw, false, nullptr, S, K, N);
+    d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
+    st = launch_gemm(d, s);
+    if (st != ZR_OK || full || policy == ZR_IMPUTE_ZERO) return st;
+    return launch_impute(Y, ldy, M, N, 1, keep_idx, n_keep, policy, prev_Y, dtype, s);
+}
+
+int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
+                          const void* dY, int64_t lddy,
+                          void* dX, int64_t lddx, void* dW, int64_t lddw,
+                          int32_t M, int32_t K, int32_t N,
+                          const int32_t* keep_idx, int32_t n_keep,
+                          int mode, int dtype, int policy,
+                          const void* prev_dX, const void* prev_dW, void* stream)
+{
+    if (!dY || (!dX && !dW)) return ZR_ERR_NULL;
+    if ((dX && !W) || (dW && !X)) return ZR_ERR_NULL;
+    int st = check_common(M, K, N, keep_idx, n_keep, mode, dtype, policy);
+    if (st != ZR_OK) return st;
+    if (lddy < N) return ZR_ERR_SHAPE;
+    if (dX && (ldw < N || lddx < K)) return ZR_ERR_SHAPE;
+    if (dW && (ldx < K || lddw < N)) return ZR_ERR_SHAPE;
+    const bool full = n_keep == (mode == ZR_DROP_N ? N : K);
+    if (policy == ZR_IMPUTE_SAME && !full) {
+        if (dW && !prev_dW) return ZR_ERR_POLICY;
+        if (dX && mode == ZR_DROP_K && !prev_dX) return ZR_ERR_POLICY;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t* S = full ? nullptr : keep_idx;
+    const bool post = !full && policy != ZR_IMPUTE_ZERO;
+
+    GemmDesc d;
+    d.dtype = dtype;
+    d.keep_idx = S;
+    if (dX) {
+        d.out = dX; d.ldo = lddx; d.I = M;
+        if (mode == ZR_DROP_K) {
+            // dX[m,S[j]] = sum_n dY[m,n] * W[S[j],n], dropped columns imputed
+            d.A = operand(dY, lddy, true, nullptr, nullptr, M, N);
+            d.B = operand(W, ldw, true, S, nullptr, K, N);
+            d.J = n_keep; d.C = N; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = K;
+        } else {
+            // dX[m,k] = sum_{c<n'} dY[m,S[c]] * W[k,S[c]]
+            d.A = operand(dY, lddy, true, nullptr, S, M, N);
+            d.B = operand(W, ldw, true, nullptr, S, K, N);
+            d.J = K; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = K;
+        }
+        st = launch_gemm(d, s);
+        if (st != ZR_OK) return st;
+        if (post && mode == ZR_DROP_K) {
+            st = launch_impute(dX, lddx, M, K, 1, keep_idx, n_keep, policy, prev_dX, dtype, s);
+            if (st != ZR_OK) return st;
+        }
+    }
+    if (dW) {
+        d.out = dW; d.ldo = lddw; d.C = M;
+        if (mode == ZR_DROP_K) {
+            // dW[S[i],n] = sum_m X[m,S[i]] * dY[m,n], dropped rows imputed
+            d.A = operand(X, ldx, false, nullptr, S, M, K);
+            d.B = operand(dY, lddy, false, nullptr, nullptr, M, N);
+            d.I = n_keep; d.J = N; d.epilogue = full ? EPI_PLAIN : EPI_ROW_SCATTER; d.out_full = K;
+        } else {
+            // dW[k,S[j]] = sum_m X[m,k] * dY[m,S[j]], dropped columns imputed
+            d.A = operand(X, ldx, false, nullptr, nullptr, M, K);
+            d.B = operand(dY, lddy, false, nullptr, S, M, N);
+            d.I = K; d.J = n_keep; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
+        }
+        st = launch_gemm(d, s);
+        if (st != ZR_OK) return st;
+        if (post) {
+            st = launch_impute(dW, lddw, K, N, mode == ZR_DROP_K ? 0 : 1, keep_idx, n_keep, policy,
+                               prev_dW, dtype, s);
+            if (st != ZR_OK) return st;
+        }
+    }
+    return ZR_OK;
+}
+
+int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
+              const int32_t* keep_idx, int32_t n_keep, int policy, const void* prev,
+              int dtype, void* stream)
+{
+    if (!out || !keep_idx) return ZR_ERR_NULL;
+    if (!valid_dtype(dtype)) return ZR_ERR_DTYPE;
+    if (!valid_policy(policy)) return ZR_ERR_POLICY;
+    if (rows < 1 || cols < 1 || ld < cols || (axis != 0 && axis != 1)) return ZR_ERR_SHAPE;
+    const int32_t n = axis == 0 ? rows : cols;
+    if (n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
+    if (policy == ZR_IMPUTE_SAME && n_keep < n && !prev) return ZR_ERR_POLICY;
+    if (rows > (1 << 21)) return ZR_ERR_LIMIT;
+    return launch_impute(out, ld, rows, cols, axis, keep_idx, n_keep, policy, prev, dtype,
+                         (hipStream_t)stream);
+}
+
+int zr_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t n,
+                         int32_t* flag, void* stream)
+{
+    if (!keep_idx || !flag) return ZR_ERR_NULL;
+    if (n < 1 || n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
+    return launch_validate(keep_idx, n_keep, n, flag, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the HIP translation units of libzr.
+// Written for gfx950 (MI355X) only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zr.h"
+
+namespace zr {
+
+// ---- bf16 <-> fp32 on raw 16-bit storage -----------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h)
+{
+    return __uint_as_float(h << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN (quietened)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// clamp an index read from a caller's list into [0, n): a malformed list may
+// give wrong values but never an out-of-range access
+__device__ __forceinline__ int clamp_idx(int v, int n)
+{
+    return v < 0 ? 0 : (v >= n ? n - 1 : v);
+}
+
+// ---- problem description handed from the C ABI to the GEMM launcher ---------
+//
+// Every product is brought to the canonical form
+//     D[i, j] = sum_c A(i, c) * B(j, c),   i < I, j < J, c < C
+// where each operand is addressed as base[rowmap(r) * ld + colmap(q)] with r the
+// index along the tensor's strided axis and q along its contiguous axis; either
+// map may be absent (identity) or the kept-index list.
+struct Operand {
+    const void* base;
+    int64_t ld;          // elements
+    // which canonical index runs along the tensor's contiguous axis
+    // true : contraction index c is contiguous  ("format P", e.g. X in Y = X W)
+    // false: the non-contraction index is contiguous ("format Q", e.g. W in Y = X W)
+    bool c_contig;
+    const int32_t* map_strided;   // list applied to the strided axis, or nullptr
+    const int32_t* map_contig;    // list applied to the contiguous axis, or nullptr
+    int n_strided;                // full extent of the strided axis in memory (for clamping)
+    int n_contig;                 // full extent of the contiguous axis in memory
+};
+
+enum Epilogue { EPI_PLAIN = 0, EPI_COL_SCATTER = 1, EPI_ROW_SCATTER = 2 };
+
+struct GemmDesc {
+    Operand A, B;
+    int I, J, C;
+    void* out;
+    int64_t ldo;
+    int epilogue;
+    const int32_t* keep_idx;   // list used by the scatter epilogues
+    int out_full;              // full extent of the scattered output axis
+    int dtype;
+};
+
+int launch_gemm(const GemmDesc& d, hipStream_t stream);
+int launch_select(const float* scores, int n, int batch, int n_keep,
+                  int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream);
+int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
+                  const int32_t* keep_idx, int n_keep, int policy, const void* prev,
+                  int dtype, hipStream_t stream);
+int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? ZR_OK : ZR_ERR_HIP; }
+
+}  // namespace zr

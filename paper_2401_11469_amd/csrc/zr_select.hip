@@ -1,0 +1,174 @@
+// Priority selection: the n' highest-score indices, emitted ascending
+// (Algorithm 1 of the paper: top-L_pri select, then ascending sort), plus the
+// complementary pruned set P of the lineage tuple (Sec. 3.1).
+//
+// No sort is needed: a 4-pass MSB radix select finds the n'-th largest order
+// key T and how many keys are strictly greater; one ordered pass over the
+// indices then keeps every index whose key is > T and the first (by index) of
+// those equal to T, writing kept and pruned indices by prefix position, which
+// makes both lists ascending by construction.
+//
+// One workgroup of 1024 threads (16 wavefronts of 64) per score vector.
+#include "zr_common.h"
+
+namespace zr {
+
+namespace {
+
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+
+// Monotone map fp32 -> uint32: larger score <=> larger key.  NaN -> 0 (lowest,
+// below -inf); -0.0 and +0.0 share one key.
+__device__ __forceinline__ uint32_t order_key(float s)
+{
+    uint32_t u = __float_as_uint(s);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN
+    if ((u & 0x7fffffffu) == 0u) u = 0u;              // -0.0 -> +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+    const float* __restrict__ scores, int n, int n_keep,
+    int32_t* __restrict__ keep_idx, int32_t* __restrict__ drop_idx, int64_t ld_idx)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_digit, s_remaining;
+    __shared__ uint32_t wave_gt[SEL_WAVES], wave_eq[SEL_WAVES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const float* s = scores + (size_t)blockIdx.x * (size_t)n;
+    int32_t* keep = keep_idx + (size_t)blockIdx.x * (size_t)ld_idx;
+    int32_t* drop = drop_idx ? drop_idx + (size_t)blockIdx.x * (size_t)ld_idx : nullptr;
+
+    // ---- radix select of the n_keep-th largest key -------------------------
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)n_keep;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += SEL_THREADS) {
+            const uint32_t k = order_key(s[i]);
+            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns bins 4l..4l+3; suffix sums give, for each bin, the
+            // number of candidates in strictly higher bins
+            uint32_t h[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) h[q] = hist[4 * lane + q];
+            const uint32_t mine = h[0] + h[1] + h[2] + h[3];
+            uint32_t incl = mine;                       // inclusive suffix sum over lanes
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t v = __shfl_down(incl, off, 64);
+                if (lane + off < 64) incl += v;
+            }
+            uint32_t above = incl - mine;               // candidates in lanes > this one
+#pragma unroll
+            for (int q = 3; q >= 0; --q) {
+                if (above < remaining && remaining <= above + h[q]) {
+                    s_digit = (uint32_t)(4 * lane + q);
+                    s_remaining = remaining - above;
+                }
+                above += h[q];
+            }
+        }
+        __syncthreads();
+        prefix |= s_digit << shift;
+        mask |= 0xffu << shift;
+        remaining = s_remaining;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;          // the n_keep-th largest key
+    const uint32_t need_eq = remaining; // how many of the keys == T are kept (>= 1)
+
+    // ---- ordered compaction -----------------------------------------------
+    uint32_t run_gt = 0, run_eq = 0;    // totals over all earlier chunks
+    for (int base = 0; base < n; base += SEL_THREADS) {
+        const int i = base + tid;
+        bool gt = false, eq = false;
+        if (i < n) {
+            const uint32_t k = order_key(s[i]);
+            gt = k > T;
+            eq = k == T;
+        }
+        const uint64_t bgt = __ballot(gt);
+        const uint64_t beq = __ballot(eq);
+        const uint64_t below = (1ull << lane) - 1ull;
+        if (lane == 0) {
+            wave_gt[wave] = (uint32_t)__popcll(bgt);
+            wave_eq[wave] = (uint32_t)__popcll(beq);
+        }
+        __syncthreads();
+        uint32_t pre_gt = run_gt + (uint32_t)__popcll(bgt & below);
+        uint32_t pre_eq = run_eq + (uint32_t)__popcll(beq & below);
+        uint32_t tot_gt = 0, tot_eq = 0;
+#pragma unroll
+        for (int w = 0; w < SEL_WAVES; ++w) {
+            const uint32_t g = wave_gt[w], e = wave_eq[w];
+            if (w < wave) { pre_gt += g; pre_eq += e; }
+            tot_gt += g;
+            tot_eq += e;
+        }
+        if (i < n) {
+            const bool kept = gt || (eq && pre_eq < need_eq);
+            // kept indices before i: all greater ones plus the first need_eq equal ones
+            const uint32_t kept_before = pre_gt + (pre_eq < need_eq ? pre_eq : need_eq);
+            // positions are in range by construction; the comparisons only make
+            // an out-of-range store impossible whatever the scores hold
+            if (kept) {
+                if (kept_before < (uint32_t)n_keep) keep[kept_before] = i;
+            } else if (drop) {
+                const uint32_t pos = (uint32_t)i - kept_before;
+                if (pos < (uint32_t)(n - n_keep)) drop[pos] = i;
+            }
+        }
+        run_gt += tot_gt;
+        run_eq += tot_eq;
+        __syncthreads();
+    }
+}
+
+__global__ void validate_kernel(const int32_t* __restrict__ keep_idx, int n_keep, int n,
+                                int32_t* __restrict__ flag)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_keep) return;
+    const int v = keep_idx[i];
+    bool bad = v < 0 || v >= n;
+    if (i > 0 && keep_idx[i - 1] >= v) bad = true;
+    if (bad) atomicOr(flag, 1);
+}
+
+}  // namespace
+
+int launch_select(const float* scores, int n, int batch, int n_keep,
+                  int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream)
+{
+    hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(SEL_THREADS), 0, stream,
+                       scores, n, n_keep, keep_idx, drop_idx, ld_idx);
+    return hip_status(hipGetLastError());
+}
+
+int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream)
+{
+    hipError_t e = hipMemsetAsync(flag, 0, sizeof(int32_t), stream);
+    if (e != hipSuccess) return ZR_ERR_HIP;
+    const int threads = 256;
+    hipLaunchKernelGGL(validate_kernel, dim3((n_keep + threads - 1) / threads), dim3(threads), 0,
+                       stream, keep_idx, n_keep, n, flag);
+    e = hipGetLastError();
+    if (e != hipSuccess) return ZR_ERR_HIP;
+    int32_t host = 0;
+    e = hipMemcpyAsync(&host, flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+    if (e != hipSuccess) return ZR_ERR_HIP;
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return ZR_ERR_HIP;
+    return host ? ZR_ERR_INDEX : ZR_OK;
+}
+
+}  // namespace zr

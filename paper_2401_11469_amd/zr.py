@@ -1,0 +1,184 @@
+"""ctypes binding of libzr.so (argument marshalling only).
+
+Functions carry the names of the C ABI in include/zr.h.  Tensors are torch
+tensors living on the GPU; only their data pointers, shapes and strides cross
+the boundary.  There is no CPU fallback: if the library is not built the
+import raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+DROP_N, DROP_K = 0, 1
+ZERO, AVERAGE, SAME = 0, 1, 2
+F32, BF16 = 0, 1
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzr.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it first (python -m paper_2401_11469_amd.build); "
+        "there is no fallback path")
+_lib = ctypes.CDLL(_LIB_PATH)
+
+_vp, _i32, _i64, _f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+
+_lib.zr_status_string.argtypes = [ctypes.c_int]
+_lib.zr_status_string.restype = ctypes.c_char_p
+_lib.zr_keep_count.argtypes = [_i64, _f64]
+_lib.zr_keep_count.restype = _i64
+_lib.zr_resize_select.argtypes = [_vp, _i32, _i32, _f64, _vp, _vp, _i64, _vp]
+_lib.zr_resize_select.restype = ctypes.c_int
+_lib.zr_resized_linear_fwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32,
+                                       _vp, _i32, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp]
+_lib.zr_resized_linear_fwd.restype = ctypes.c_int
+_lib.zr_resized_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
+                                       _i32, _i32, _i32, _vp, _i32,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]
+_lib.zr_resized_linear_bwd.restype = ctypes.c_int
+_lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, ctypes.c_int, _vp]
+_lib.zr_impute.restype = ctypes.c_int
+_lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
+_lib.zr_validate_keep_idx.restype = ctypes.c_int
+
+
+class ZrError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libzr status {status}: {_lib.zr_status_string(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise ZrError(status)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _mat(t: Optional[torch.Tensor], name: str):
+    """(pointer, leading dimension) of a 2-D row-major CUDA tensor."""
+    if t is None:
+        return None, 0
+    if not t.is_cuda or t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name}: need a 2-D GPU tensor with unit column stride")
+    return t.data_ptr(), t.stride(0)
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def keep_count(n: int, ratio: float) -> int:
+    return int(_lib.zr_keep_count(n, ratio))
+
+
+def status_string(status: int) -> str:
+    return _lib.zr_status_string(status).decode()
+
+
+def resize_select(scores: torch.Tensor, ratio: float, keep_idx: Optional[torch.Tensor] = None,
+                  drop_idx: Optional[torch.Tensor] = None, want_drop: bool = True,
+                  stream=None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """scores: fp32 [n] or [batch, n] on the GPU.  Returns (keep_idx, drop_idx) as int32
+    tensors of row length n' and n - n' (views of buffers with a common pitch)."""
+    if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
+        raise ValueError("scores: need a contiguous fp32 GPU tensor")
+    batched = scores.dim() == 2
+    n = scores.shape[-1]
+    batch = scores.shape[0] if batched else 1
+    n_keep = keep_count(n, ratio)
+    if n_keep < 1:
+        raise ZrError(3)
+    ld = max(n_keep, n - n_keep, 1)
+    if keep_idx is None:
+        keep_idx = torch.empty((batch, ld), dtype=torch.int32, device=scores.device)
+    if drop_idx is None and want_drop:
+        drop_idx = torch.empty((batch, ld), dtype=torch.int32, device=scores.device)
+    for t in (keep_idx, drop_idx):
+        if t is not None and (t.dtype != torch.int32 or t.dim() != 2 or t.stride(1) != 1
+                              or t.stride(0) != keep_idx.stride(0) or t.shape[0] < batch):
+            raise ValueError("index buffers: int32 [batch, ld] with a common pitch")
+    _check(_lib.zr_resize_select(scores.data_ptr(), n, batch, float(ratio), keep_idx.data_ptr(),
+                                 None if drop_idx is None else drop_idx.data_ptr(),
+                                 keep_idx.stride(0), _stream(stream)))
+    k = keep_idx[:batch, :n_keep]
+    d = None if drop_idx is None else drop_idx[:batch, :n - n_keep]
+    if not batched:
+        k = k[0]
+        d = None if d is None else d[0]
+    return k, d
+
+
+def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor, mode: int,
+                       policy: int = ZERO, prev_Y: Optional[torch.Tensor] = None,
+                       Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = X.shape
+    N = W.shape[1]
+    if W.shape[0] != K or W.dtype != X.dtype:
+        raise ValueError("W must be [K, N] with X's dtype")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    (xp, ldx), (wp, ldw), (yp, ldy) = _mat(X, "X"), _mat(W, "W"), _mat(Y, "Y")
+    pp, ldp = _mat(prev_Y, "prev_Y")
+    if prev_Y is not None and ldp != ldy:
+        raise ValueError("prev_Y must share Y's leading dimension")
+    _check(_lib.zr_resized_linear_fwd(xp, ldx, wp, ldw, yp, ldy, M, K, N,
+                                      keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
+                                      policy, pp, _stream(stream)))
+    return Y
+
+
+def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_idx: torch.Tensor,
+                       mode: int, policy: int = ZERO, prev_dX: Optional[torch.Tensor] = None,
+                       prev_dW: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
+                       dW: Optional[torch.Tensor] = None, need_dX: bool = True, need_dW: bool = True,
+                       stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    M, K = X.shape
+    N = W.shape[1]
+    if dY.shape != (M, N):
+        raise ValueError("dY must be [M, N]")
+    if need_dX and dX is None:
+        dX = torch.empty((M, K), dtype=X.dtype, device=X.device)
+    if need_dW and dW is None:
+        dW = torch.empty((K, N), dtype=X.dtype, device=X.device)
+    (xp, ldx), (wp, ldw), (gp, ldg) = _mat(X, "X"), _mat(W, "W"), _mat(dY, "dY")
+    (dxp, lddx), (dwp, lddw) = _mat(dX if need_dX else None, "dX"), _mat(dW if need_dW else None, "dW")
+    (pxp, ldpx), (pwp, ldpw) = _mat(prev_dX, "prev_dX"), _mat(prev_dW, "prev_dW")
+    if (prev_dX is not None and need_dX and ldpx != lddx) or (prev_dW is not None and need_dW and ldpw != lddw):
+        raise ValueError("previous tensors must share the outputs' leading dimensions")
+    _check(_lib.zr_resized_linear_bwd(xp, ldx, wp, ldw, gp, ldg, dxp, lddx, dwp, lddw, M, K, N,
+                                      keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
+                                      policy, pxp, pwp, _stream(stream)))
+    return (dX if need_dX else None), (dW if need_dW else None)
+
+
+def impute(out: torch.Tensor, axis: int, keep_idx: torch.Tensor, policy: int = ZERO,
+           prev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """In place: fills the slices of ``out`` not listed in keep_idx along ``axis``."""
+    op, ld = _mat(out, "out")
+    pp, ldp = _mat(prev, "prev")
+    if prev is not None and ldp != ld:
+        raise ValueError("prev must share out's leading dimension")
+    _check(_lib.zr_impute(op, ld, out.shape[0], out.shape[1], axis, keep_idx.data_ptr(),
+                          keep_idx.numel(), policy, pp, _dtype_code(out), _stream(stream)))
+    return out
+
+
+def validate_keep_idx(keep_idx: torch.Tensor, n: int, stream=None) -> bool:
+    flag = torch.zeros(1, dtype=torch.int32, device=keep_idx.device)
+    st = _lib.zr_validate_keep_idx(keep_idx.data_ptr(), keep_idx.numel(), n, flag.data_ptr(), _stream(stream))
+    if st == 0:
+        return True
+    if st == 4:
+        return False
+    raise ZrError(st)

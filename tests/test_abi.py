@@ -1,0 +1,98 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-only logic (kept count, status strings, argument
+validation that returns before any GPU call) behaves as documented."""
+import ctypes
+import math
+import os
+import re
+from fractions import Fraction
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2401_11469_amd", "libzr.so")
+HEADER = os.path.join(ROOT, "include", "zr.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2401_11469_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert {"zr_keep_count", "zr_resize_select", "zr_resized_linear_fwd", "zr_resized_linear_bwd",
+            "zr_impute", "zr_validate_keep_idx", "zr_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_keep_count_host_function(lib):
+    f = lib.zr_keep_count
+    f.argtypes = [ctypes.c_int64, ctypes.c_double]
+    f.restype = ctypes.c_int64
+    assert f(4, 0.5) == 2 and f(10, 0.25) == 8 and f(256, 0.25) == 192 and f(7, 0.0) == 7
+    assert f(8, 1.0) == -1 and f(8, -0.5) == -1 and f(8, float("nan")) == -1 and f(-1, 0.5) == -1
+    for n in (256, 768, 1024, 2048, 2752, 3072, 1920, 640, 1728, 4096, 5120):
+        for j in range(20):
+            r = j / 20
+            assert f(n, r) == math.floor((1 - Fraction(r)) * n + Fraction(1, 2))
+
+
+def test_status_strings(lib):
+    f = lib.zr_status_string
+    f.argtypes = [ctypes.c_int]
+    f.restype = ctypes.c_char_p
+    seen = {f(i) for i in range(10)}
+    assert len(seen) == 10 and f(0) == b"ok" and f(99) == b"unknown status"
+
+
+def test_argument_validation_returns_before_any_gpu_work(lib):
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    fwd = lib.zr_resized_linear_fwd
+    fwd.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
+                    ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    fwd.restype = ctypes.c_int
+    p = 0x1000  # never dereferenced: every call below fails validation first
+    assert fwd(None, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None) == 1      # NULL
+    assert fwd(p, 8, p, 8, p, 8, 0, 8, 8, p, 4, 0, 1, 0, None, None) == 2          # M < 1
+    assert fwd(p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None) == 2          # ldx < K
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 9, 0, 1, 0, None, None) == 4          # n_keep > n
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 0, 0, 1, 0, None, None) == 4          # n_keep < 1
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 7, 0, None, None) == 5          # dtype
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 5, 1, 0, None, None) == 6          # mode
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 9, None, None) == 7          # policy
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 2, None, None) == 7          # SAME without prev
+    sel = lib.zr_resize_select
+    sel.argtypes = [vp, i32, i32, ctypes.c_double, vp, vp, i64, vp]
+    sel.restype = ctypes.c_int
+    assert sel(None, 8, 1, 0.5, p, None, 8, None) == 1
+    assert sel(p, 0, 1, 0.5, p, None, 8, None) == 2
+    assert sel(p, 8, 1, 1.0, p, None, 8, None) == 3
+    assert sel(p, 8, 1, 0.99, p, None, 8, None) == 3                                # keeps nothing
+    assert sel(p, 8, 1, 0.5, p, None, 3, None) == 2                                 # ld_idx too small
+    assert sel(p, (1 << 24) + 1, 1, 0.5, p, None, 1 << 25, None) == 8
+    imp = lib.zr_impute
+    imp.argtypes = [vp, i64, i32, i32, i32, vp, i32, ctypes.c_int, vp, ctypes.c_int, vp]
+    imp.restype = ctypes.c_int
+    assert imp(None, 8, 4, 8, 1, p, 4, 0, None, 1, None) == 1
+    assert imp(p, 4, 4, 8, 1, p, 4, 0, None, 1, None) == 2
+    assert imp(p, 8, 4, 8, 2, p, 4, 0, None, 1, None) == 2
+    assert imp(p, 8, 4, 8, 1, p, 9, 0, None, 1, None) == 4
+    assert imp(p, 8, 4, 8, 1, p, 4, 2, None, 1, None) == 7
+    bwd = lib.zr_resized_linear_bwd
+    bwd.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
+                    ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp]
+    bwd.restype = ctypes.c_int
+    assert bwd(p, 8, p, 8, p, 8, None, 8, None, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, None) == 1
+    assert bwd(p, 8, p, 8, p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, None) == 2
+    assert bwd(p, 8, p, 8, p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 1, 1, 2, None, None, None) == 7

@@ -1,0 +1,311 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Index work is bit-exact; floating point is
+compared with the relative Frobenius error: <= 1e-5 for fp32, <= 2e-2 for bf16
+inputs with fp32 accumulation; imputed positions are bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2401_11469_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DROP_N, DROP_K = 0, 1
+ZERO, AVERAGE, SAME = 0, 1, 2
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def zr():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2401_11469_amd import zr as binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    return torch
+
+
+def _tdtype(torch, dtype):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def to_gpu(torch, a, dtype, ld=None):
+    """Upload an fp32 numpy array (already bf16-representable if dtype is bf16);
+    ld > cols embeds it in a wider buffer filled with a canary."""
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(_tdtype(torch, dtype))
+    if ld is None:
+        return t.cuda()
+    buf = torch.full((a.shape[0], ld), 777.0, dtype=t.dtype, device="cuda")
+    buf[:, :a.shape[1]] = t.cuda()
+    return buf[:, :a.shape[1]]
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def relf(got, want):
+    den = np.linalg.norm(want)
+    return np.linalg.norm(got - want) / (den if den > 0 else 1.0)
+
+
+def idx_gpu(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def subset(seed, n, n_keep):
+    g = np.random.Generator(np.random.PCG64(seed))
+    return np.sort(g.choice(n, size=n_keep, replace=False)).astype(np.int32)
+
+
+# ------------------------------------------------------------------ select ---
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 256, 640, 1000, 1024, 1025, 2752, 5120, 40000])
+@pytest.mark.parametrize("kind", ["normal", "ties", "uniform"])
+def test_select_bit_exact(zr, torch_mod, oracle, n, kind):
+    torch = torch_mod
+    s = wl.random_case(100 + n, 1, n, 1, score_kind=kind)["scores_K"]
+    sg = torch.from_numpy(s).cuda()
+    for ratio in (0.0, 0.05, 0.25, 0.5, 0.9):
+        if oracle.keep_count(n, ratio) < 1:
+            continue
+        keep, drop = zr.resize_select(sg, ratio)
+        ok, od = oracle.resize_select(s, ratio)
+        assert keep.dtype == torch.int32
+        assert np.array_equal(keep.cpu().numpy(), ok), (n, kind, ratio)
+        assert np.array_equal(drop.cpu().numpy(), od), (n, kind, ratio)
+        assert zr.keep_count(n, ratio) == oracle.keep_count(n, ratio)
+
+
+def test_select_special_values_and_batch(zr, torch_mod, oracle):
+    torch = torch_mod
+    s = np.array([np.nan, -0.0, 0.0, np.inf, -np.inf, 1.0, np.nan, 0.0, -1.0, 1.0, -np.nan, 3e38],
+                 dtype=np.float32)
+    for ratio in (0.0, 0.1, 0.25, 0.4, 0.5, 0.75, 0.9):
+        keep, drop = zr.resize_select(torch.from_numpy(s).cuda(), ratio)
+        ok, od = oracle.resize_select(s, ratio)
+        assert np.array_equal(keep.cpu().numpy(), ok) and np.array_equal(drop.cpu().numpy(), od)
+    # batched: one workgroup per vector, the config-4 projections' axis lengths padded to one n
+    g = np.random.Generator(np.random.PCG64(5))
+    B, n = 37, 3072
+    S = g.standard_normal((B, n)).astype(np.float32)
+    S[3, :] = 1.0                     # all tied: the lowest indices are kept
+    S[4, ::2] = np.nan
+    keep, drop = zr.resize_select(torch.from_numpy(S).cuda(), 0.35)
+    for b in range(B):
+        ok, od = oracle.resize_select(S[b], 0.35)
+        assert np.array_equal(keep[b].cpu().numpy(), ok) and np.array_equal(drop[b].cpu().numpy(), od)
+    assert keep[3].cpu().numpy().tolist() == list(range(oracle.keep_count(n, 0.35)))
+
+
+def test_select_on_config_scores(zr, torch_mod, oracle):
+    torch = torch_mod
+    for cid, cfg in wl.CONFIGS.items():
+        for pi, pr in enumerate(cfg.projections):
+            s = wl.make_scores(cid, pi)
+            assert s.shape == (pr.n_axis,)
+            for r in cfg.ratios:
+                r = wl.ratio_for(cfg, pr, r)
+                keep, drop = zr.resize_select(torch.from_numpy(s).cuda(), r)
+                ok, od = oracle.resize_select(s, r)
+                assert np.array_equal(keep.cpu().numpy(), ok) and np.array_equal(drop.cpu().numpy(), od)
+                assert zr.validate_keep_idx(keep, pr.n_axis)
+
+
+def test_validate_keep_idx(zr, torch_mod):
+    torch = torch_mod
+    assert zr.validate_keep_idx(idx_gpu(torch, [0, 3, 4]), 5)
+    assert not zr.validate_keep_idx(idx_gpu(torch, [0, 3, 3]), 5)
+    assert not zr.validate_keep_idx(idx_gpu(torch, [0, 3, 5]), 5)
+    assert not zr.validate_keep_idx(idx_gpu(torch, [-1, 3, 4]), 5)
+
+
+# ------------------------------------------------------------------ impute ---
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("policy", [ZERO, AVERAGE, SAME])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (5, 7), (33, 300), (300, 33), (129, 1031)])
+def test_impute_parity(zr, torch_mod, oracle, dtype, axis, policy, rows, cols):
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(rows * 131 + cols))
+    cast = wl.round_to_bf16 if dtype == "bf16" else (lambda x: x)
+    out = cast(g.standard_normal((rows, cols)).astype(np.float32))
+    prev = cast(g.standard_normal((rows, cols)).astype(np.float32))
+    n = rows if axis == 0 else cols
+    for n_keep in sorted({1, max(1, n // 2), max(1, n - 1), n}):
+        S = subset(n_keep + 17, n, n_keep)
+        ld = cols + 5
+        og = to_gpu(torch, out, dtype, ld=ld)
+        pg = to_gpu(torch, prev, dtype, ld=ld)
+        zr.impute(og, axis, idx_gpu(torch, S), policy, pg if policy == SAME else None)
+        want = oracle.impute(out, axis, S, policy, prev)
+        got = to_np(og)
+        drop = np.setdiff1d(np.arange(n), S)
+        kept_got = got[S, :] if axis == 0 else got[:, S]
+        kept_in = out[S, :] if axis == 0 else out[:, S]
+        assert np.array_equal(kept_got, kept_in.astype(np.float64))      # kept slices untouched
+        dg = got[drop, :] if axis == 0 else got[:, drop]
+        dw = want[drop, :] if axis == 0 else want[:, drop]
+        if policy in (ZERO, SAME):
+            assert np.array_equal(dg, dw)
+            if policy == ZERO:
+                assert not np.any(np.signbit(dg))
+        elif drop.size:
+            # mean of up to n values of size ~1 in fp32, then one rounding to the dtype
+            atol = 1e-5 if dtype == "f32" else 2.0 ** -8
+            assert np.max(np.abs(dg - dw)) <= atol * max(1.0, np.max(np.abs(dw)))
+        # the padding between rows is never written
+        base = og._base if og._base is not None else og
+        assert torch.all(base[:, cols:] == 777.0)
+
+
+# ------------------------------------------------------------------- GEMMs ---
+
+def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0):
+    """fwd + bwd through the C ABI; returns float64 numpy (Y, dX, dW)."""
+    M, K = case["X"].shape
+    N = case["W"].shape[1]
+    ld = (lambda c: c + pad) if pad else (lambda c: None)
+    X = to_gpu(torch, case["X"], dtype, ld(K))
+    W = to_gpu(torch, case["W"], dtype, ld(N))
+    dY = to_gpu(torch, case["dY"], dtype, ld(N))
+    keep = idx_gpu(torch, S)
+    pY = to_gpu(torch, case["prev_Y"], dtype, ld(N)) if policy == SAME else None
+    pdX = to_gpu(torch, case["prev_dX"], dtype, ld(K)) if policy == SAME else None
+    pdW = to_gpu(torch, case["prev_dW"], dtype, ld(N)) if policy == SAME else None
+    Y = to_gpu(torch, np.full((M, N), 555.0, np.float32), dtype, ld(N))
+    dX = to_gpu(torch, np.full((M, K), 555.0, np.float32), dtype, ld(K))
+    dW = to_gpu(torch, np.full((K, N), 555.0, np.float32), dtype, ld(N))
+    zr.resized_linear_fwd(X, W, keep, mode, policy, pY, Y=Y)
+    zr.resized_linear_bwd(X, W, dY, keep, mode, policy, pdX, pdW, dX=dX, dW=dW)
+    torch.cuda.synchronize()
+    if pad:
+        for t in (Y, dX, dW):
+            assert torch.all(t._base[:, t.shape[1]:] == 777.0), "padding overwritten"
+    return to_np(Y), to_np(dX), to_np(dW)
+
+
+def check_layer(oracle, case, S, mode, dtype, policy, got, tol=None):
+    tol = TOL[dtype] if tol is None else tol
+    M, K = case["X"].shape
+    N = case["W"].shape[1]
+    wantY = oracle.resized_linear_fwd(case["X"], case["W"], S, mode, policy, case.get("prev_Y"))
+    wantdX, wantdW = oracle.resized_linear_bwd(case["X"], case["W"], case["dY"], S, mode, policy,
+                                               case.get("prev_dX"), case.get("prev_dW"))
+    names = ("Y", "dX", "dW")
+    for name, g, w in zip(names, got, (wantY, wantdX, wantdW)):
+        assert g.shape == w.shape
+        assert np.all(np.isfinite(g)), name
+        e = relf(g, w)
+        assert e <= tol, (name, e)
+    # imputed positions: bit-exact for Zero / Same
+    n = N if mode == DROP_N else K
+    P = np.setdiff1d(np.arange(n), S)
+    if P.size and policy in (ZERO, SAME):
+        Y, dX, dW = got
+        if mode == DROP_K:
+            pairs = [(dX[:, P], wantdX[:, P]), (dW[P, :], wantdW[P, :])]
+        else:
+            pairs = [(Y[:, P], wantY[:, P]), (dW[:, P], wantdW[:, P])]
+        for g, w in pairs:
+            assert np.array_equal(g, w)
+            if policy == ZERO:
+                assert not np.any(np.signbit(g))
+    return wantY, wantdX, wantdW
+
+
+SMALL_SHAPES = [(1, 1, 1), (3, 5, 7), (64, 64, 64), (130, 200, 136), (257, 130, 300), (96, 520, 264)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("M,K,N", SMALL_SHAPES)
+def test_layer_parity_small_and_ragged(zr, torch_mod, oracle, dtype, mode, M, K, N):
+    torch = torch_mod
+    case = wl.random_case(1000 + M + 7 * K + 13 * N, M, K, N, dtype)
+    n = N if mode == DROP_N else K
+    for n_keep in sorted({1, max(1, n // 2), max(1, (3 * n) // 4), max(1, n - 1), n}):
+        S = subset(n_keep * 31 + n, n, n_keep)
+        got = run_layer(zr, torch, case, S, mode, dtype)
+        check_layer(oracle, case, S, mode, dtype, ZERO, got)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+def test_layer_parity_unaligned_leading_dimensions(zr, torch_mod, oracle, dtype, mode):
+    """ld not a multiple of the vector width: element-wise paths; the padding
+    columns between rows must stay untouched."""
+    torch = torch_mod
+    M, K, N = 150, 139, 203
+    case = wl.random_case(4242, M, K, N, dtype)
+    n = N if mode == DROP_N else K
+    for n_keep in (n, (2 * n) // 3):
+        S = subset(n_keep, n, n_keep)
+        got = run_layer(zr, torch, case, S, mode, dtype, pad=3)
+        check_layer(oracle, case, S, mode, dtype, ZERO, got)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("policy", [AVERAGE, SAME])
+def test_layer_parity_other_policies(zr, torch_mod, oracle, dtype, mode, policy):
+    torch = torch_mod
+    M, K, N = 140, 264, 200
+    case = wl.random_case(777, M, K, N, dtype)
+    n = N if mode == DROP_N else K
+    S = subset(9, n, (3 * n) // 5)
+    got = run_layer(zr, torch, case, S, mode, dtype, policy)
+    check_layer(oracle, case, S, mode, dtype, policy, got)
+
+
+def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
+    """Kept sets that are a prefix, a suffix, every other index, or one far
+    index: the scatter epilogue's ownership ranges degenerate in each."""
+    torch = torch_mod
+    M, K, N = 200, 300, 280
+    case = wl.random_case(99, M, K, N, "bf16")
+    for mode in (DROP_N, DROP_K):
+        n = N if mode == DROP_N else K
+        sets = [np.arange(0, n // 2), np.arange(n // 2, n), np.arange(0, n, 2), np.arange(1, n, 2),
+                np.array([n - 1]), np.array([0]), np.array([0, n - 1]),
+                np.concatenate([np.arange(0, 5), np.arange(n - 130, n)])]
+        for S in sets:
+            S = S.astype(np.int32)
+            got = run_layer(zr, torch, case, S, mode, "bf16")
+            check_layer(oracle, case, S, mode, "bf16", ZERO, got)
+
+
+def test_bitwise_repeatable(zr, torch_mod):
+    torch = torch_mod
+    case = wl.random_case(5, 300, 520, 390, "bf16")
+    for mode in (DROP_N, DROP_K):
+        n = 390 if mode == DROP_N else 520
+        S = subset(3, n, (2 * n) // 3)
+        a = run_layer(zr, torch, case, S, mode, "bf16")
+        b = run_layer(zr, torch, case, S, mode, "bf16")
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+
+
+def test_config1_full(zr, torch_mod, oracle):
+    """Tiny column-parallel fp32 layer: select by column L2 norm at ratio 0.25,
+    then forward and backward, everything against the oracle."""
+    torch = torch_mod
+    cfg = wl.CONFIGS[1]
+    t = wl.make_tensors(1, 0)
+    scores = wl.make_scores(1, 0, t["W"])
+    keep, drop = zr.resize_select(torch.from_numpy(scores).cuda(), 0.25)
+    ok, od = oracle.resize_select(scores, 0.25)
+    assert len(ok) == 192 and np.array_equal(keep.cpu().numpy(), ok) and np.array_equal(drop.cpu().numpy(), od)
+    got = run_layer(zr, torch, t, ok, DROP_N, "f32")
+    check_layer(oracle, t, ok, DROP_N, "f32", ZERO, got)
+    # ratio 0 reproduces the full shard GEMM
+    full = np.arange(256, dtype=np.int32)
+    got = run_layer(zr, torch, t, full, DROP_N, "f32")
+    X, W, dY = (t[k].astype(np.float64) for k in ("X", "W", "dY"))
+    for g, w in zip(got, (X @ W, dY @ W.T, X.T @ dY)):
+        assert relf(g, w) <= 1e-5
