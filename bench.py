@@ -1,0 +1,218 @@
+"""Benchmark of the resized tensor-parallel shard GEMMs on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input for
+every projection of the workload's layer shard: resize_select (scores ->
+kept/dropped index lists), resized_linear_fwd, resized_linear_bwd (dX and dW)
+with the scatter + Zero-imputation epilogue.  The step's pruning ratio is
+drawn from a seeded sequence over the workload's ratio list (time-varying
+straggler contention).  The metric is effective TFLOP/s over the KEPT work
+(6*M*K*N*n'/n per projection) with all inputs resident in HBM.
+
+Prints ONE JSON line.  One GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
+HBM_PEAK_GBS = 8000.0
+
+
+def kernel_label(op: str, mode: int, full: bool, dtype: str) -> str:
+    """Name of the gemm_kernel instantiation a product runs on, as rocprofv3
+    prints it: <dtype, A contraction-contiguous, A vector loads, B contraction-
+    contiguous, B vector loads, BM, BN>."""
+    dt = 1 if dtype == "bf16" else 0
+    fmt = {"fwd": (True, False), "dX": (True, True), "dW": (False, False)}[op]
+    if full:
+        vec = (True, True)
+    else:
+        vec = {("fwd", 1): (False, True), ("fwd", 0): (True, False),
+               ("dX", 1): (True, True), ("dX", 0): (False, False),
+               ("dW", 1): (False, True), ("dW", 0): (True, False)}[(op, mode)]
+    b = lambda v: "true" if v else "false"
+    return f"gemm_kernel<{dt}, {b(fmt[0])}, {b(vec[0])}, {b(fmt[1])}, {b(vec[1])}, 128, 128>"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = Llama-2-7B TP=4 layer shard)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one tensor-parallel task's shard on ONE GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of this build)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2401_11469_amd import workloads as wl
+    from paper_2401_11469_amd import zr
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    M = cfg.M
+
+    # ---- inputs resident in HBM before any timing ---------------------------
+    projs = []
+    for pi, pr in enumerate(cfg.projections):
+        t = wl.make_tensors(args.config, pi)
+        scores = wl.make_scores(args.config, pi, t["W"])
+        n = pr.n_axis
+        projs.append(dict(
+            pr=pr, n=n,
+            X=torch.from_numpy(t["X"]).to(tdt).to(dev), W=torch.from_numpy(t["W"]).to(tdt).to(dev),
+            dY=torch.from_numpy(t["dY"]).to(tdt).to(dev), scores=torch.from_numpy(scores).to(dev),
+            Y=torch.empty((M, pr.N), dtype=tdt, device=dev), dX=torch.empty((M, pr.K), dtype=tdt, device=dev),
+            dW=torch.empty((pr.K, pr.N), dtype=tdt, device=dev),
+            keep=torch.empty((1, n), dtype=torch.int32, device=dev),
+            drop=torch.empty((1, n), dtype=torch.int32, device=dev)))
+        del t
+    torch.cuda.synchronize()
+
+    def step_flops(ratio: float) -> float:
+        return sum(wl.kept_flops(M, p["pr"].K, p["pr"].N, p["n"],
+                                 zr.keep_count(p["n"], wl.ratio_for(cfg, p["pr"], ratio))) for p in projs)
+
+    def run_step(ratio: float, events=None):
+        for p in projs:
+            pr = p["pr"]
+            r = wl.ratio_for(cfg, pr, ratio)
+            keep, _ = zr.resize_select(p["scores"], r, keep_idx=p["keep"], drop_idx=p["drop"])
+            full = keep.numel() == p["n"]
+            if events is None:
+                zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"])
+                zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"])
+            else:
+                fl = 2.0 * M * pr.K * pr.N * keep.numel() / p["n"]
+                for op in ("fwd", "dX", "dW"):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    if op == "fwd":
+                        zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"])
+                    elif op == "dX":
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], need_dW=False)
+                    else:
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False)
+                    e1.record()
+                    events.append((kernel_label(op, pr.mode, full, cfg.dtype), fl, e0, e1))
+
+    ratios = wl.ratio_sequence(args.config, args.warmup + args.steps)
+
+    # ---- timed region: exactly --steps steps, events on the launch stream ----
+    for r in ratios[:args.warmup]:
+        run_step(r)
+    torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    t0.record()
+    for r in ratios[args.warmup:]:
+        run_step(r)
+    t1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    gpu_ms = t0.elapsed_time(t1)
+    total_ms = max(gpu_ms, wall * 1e3)        # host-launch-bound runs are charged the wall clock
+    flops = sum(step_flops(r) for r in ratios[args.warmup:])
+    value = flops / (total_ms * 1e-3) / 1e12
+
+    # ---- per-kernel durations (same steps again, one event pair per launch) --
+    events = []
+    for r in ratios[args.warmup:]:
+        run_step(r, events)
+    torch.cuda.synchronize()
+    per = {}
+    for label, fl, e0, e1 in events:
+        d = per.setdefault(label, [0, 0.0, 0.0])
+        d[0] += 1
+        d[1] += fl
+        d[2] += e0.elapsed_time(e1)
+    kernels = {k: {"launches": v[0], "avg_ms": v[2] / v[0], "tflops": v[1] / (v[2] * 1e-3) / 1e12}
+               for k, v in per.items()}
+    dom = max(per.items(), key=lambda kv: kv[1][2])
+    peak = PEAK_TFLOPS[cfg.dtype]
+    dom_tflops = dom[1][1] / (dom[1][2] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s",
+                "frac": dom_tflops / peak, "traffic": None,
+                "avg_launch_ms": dom[1][2] / dom[1][0], "launches": dom[1][0]}
+
+    # ---- time vs ratio (median of a few steps each) --------------------------
+    sweep = {}
+    if not args.no_sweep:
+        base_ms = None
+        for r in cfg.ratios:
+            ms = []
+            for _ in range(5):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run_step(r)
+                b.record()
+                torch.cuda.synchronize()
+                ms.append(a.elapsed_time(b))
+            med = float(np.median(ms))
+            if base_ms is None:
+                base_ms = med
+            fl = step_flops(r)
+            sweep[f"{r:.2f}"] = {"ms": med, "tflops": fl / (med * 1e-3) / 1e12,
+                                 "frac_peak": fl / (med * 1e-3) / 1e12 / peak,
+                                 "speedup_vs_first": base_ms / med,
+                                 "kept_fraction": fl / step_flops(cfg.ratios[0])}
+
+    # ---- CPU oracle on the host cores, bounded sample -------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        m_slice = min(M, 1024)
+        ratio = 0.25
+        work = 0.0
+        secs = 0.0
+        for pi, pr in enumerate(cfg.projections):
+            t = wl.make_tensors(args.config, pi, M=m_slice)
+            scores = wl.make_scores(args.config, pi, t["W"])
+            r = wl.ratio_for(cfg, pr, ratio)
+            c0 = time.perf_counter()
+            keep, _ = oracle.resize_select(scores, r)
+            oracle.resized_linear_fwd(t["X"], t["W"], keep, pr.mode)
+            oracle.resized_linear_bwd(t["X"], t["W"], t["dY"], keep, pr.mode)
+            secs += time.perf_counter() - c0
+            work += wl.kept_flops(m_slice, pr.K, pr.N, pr.n_axis, len(keep))
+        cpu = {"value": work / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{cfg.name}: all {len(cfg.projections)} projections, select+fwd+bwd at ratio {ratio}, "
+                         f"first-M slice of {m_slice} tokens (fresh draw), float64, {secs:.1f} s"}
+
+    line = {
+        "metric": "effective TFLOP/s (fwd+bwd) of resized TP shard GEMM vs resize ratio; % MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": total_ms / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: M={M} tokens, projections "
+                               + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
+                               + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
+                   "path": "resize_select + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation"},
+        "frac_mfma_peak": value / peak,
+        "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "by_ratio": sweep,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
