@@ -64,6 +64,7 @@ struct GemmDesc {
 };
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
+int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,
                   int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream);
 int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,

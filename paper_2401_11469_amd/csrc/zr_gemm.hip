@@ -595,6 +595,8 @@ int launch_dt(const GemmDesc& d, hipStream_t stream)
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream)
 {
+    const int fast = launch_gemm_fast(d, stream);   // bf16, 16-byte aligned rows
+    if (fast >= 0) return fast;
     if (d.dtype == ZR_BF16) return launch_dt<ZR_BF16>(d, stream);
     if (d.dtype == ZR_F32) return launch_dt<ZR_F32>(d, stream);
     return ZR_ERR_DTYPE;
