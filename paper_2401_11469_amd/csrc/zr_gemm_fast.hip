@@ -27,13 +27,26 @@ namespace zr {
 
 namespace {
 
-constexpr int BKD = 32;          // contraction depth of one LDS tile in 32-bit words (64 bf16)
-constexpr int BK = 64;
-constexpr int PP = BKD + 4;      // row pitch of format P (words)
+constexpr int BK = 64;           // contraction depth of one LDS tile (bf16 elements)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint16_t E;
+
+// LDS tile layout, the same for every operand kind: 8 blocks (one per group of
+// 8 contraction indices); inside a block every tile row owns one 16-byte slot
+// holding its 8 bf16 of that group, so an MFMA k-vector is one ds_read_b128.
+// The LDS serves 16-byte accesses 8 lanes at a time over 32 banks (128 bytes):
+// 8 consecutive lanes must hit 8 different slots modulo 8.  Rows are placed at
+// slot(i) = i + (i >> 3), which gives that both for 8 consecutive rows (fragment
+// reads, row-wise writes) and for rows 8 apart (writes of the loaders whose
+// lanes hold 8 consecutive columns each); blocks are 1 slot out of phase so
+// that lanes writing the same row of different blocks do not collide either.
+template <int R> struct Tile {
+    static constexpr int BW = (R + R / 8 + 1) * 4;    // words per block
+    static constexpr int WORDS = 8 * BW;
+    static __device__ __forceinline__ int slot(int i) { return i + (i >> 3); }
+};
 
 struct FOp {
     const E* base;
@@ -78,15 +91,21 @@ __device__ __forceinline__ int lower_bound_lds(const int* s, int n, int p)
     return lo;
 }
 
-// (c, c+1) interleave of two memory rows holding 8 consecutive columns each
-__device__ __forceinline__ void interleave8(const uint4& lo, const uint4& hi, uint32_t w[8])
+// Four memory rows (contraction indices c..c+3) x 8 consecutive columns ->
+// for column m the two words (c,c+1) and (c+2,c+3).
+__device__ __forceinline__ void interleave4x8(const uint4 r[4], uint2 w[8])
 {
-    const uint32_t a[4] = {lo.x, lo.y, lo.z, lo.w};
-    const uint32_t b[4] = {hi.x, hi.y, hi.z, hi.w};
+    const uint32_t a[4] = {r[0].x, r[0].y, r[0].z, r[0].w};
+    const uint32_t b[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
+    const uint32_t c[4] = {r[2].x, r[2].y, r[2].z, r[2].w};
+    const uint32_t d[4] = {r[3].x, r[3].y, r[3].z, r[3].w};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        w[2 * t] = (a[t] & 0xffffu) | (b[t] << 16);
-        w[2 * t + 1] = (a[t] >> 16) | (b[t] & 0xffff0000u);
+        // v_perm byte selectors: 0-3 = second source, 4-7 = first source
+        w[2 * t] = make_uint2(__builtin_amdgcn_perm(b[t], a[t], 0x05040100u),
+                              __builtin_amdgcn_perm(d[t], c[t], 0x05040100u));
+        w[2 * t + 1] = make_uint2(__builtin_amdgcn_perm(b[t], a[t], 0x07060302u),
+                                  __builtin_amdgcn_perm(d[t], c[t], 0x07060302u));
     }
 }
 
@@ -98,14 +117,15 @@ __device__ __forceinline__ void interleave8(const uint4& lo, const uint4& hi, ui
 // tile k+1 stay in flight during the MFMAs of tile k.
 // ---------------------------------------------------------------------------
 
-// Format P, 16-byte loads, optional row list.
+// Contraction axis contiguous in memory, 16-byte loads, optional row list.
 template <int R, int NT>
 struct LdPV {
+    typedef Tile<R> T;
     static constexpr int N = R * 8 / NT;
-    static constexpr int WORDS = R * PP;
     static constexpr bool NEEDS_IDX = false;
     const E* ptr[N];
     uint4 v[N];
+    bool ok_;               // the fetched chunk lies inside the contraction range
 
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int)
     {
@@ -120,28 +140,29 @@ struct LdPV {
     __device__ __forceinline__ void fetch(const FOp&, int c0, int C, int tid)
     {
         const int c = c0 + (tid & 7) * 8;            // C is a multiple of 8 on this path
-        const bool ok = c < C;
-        const int cc = ok ? c0 : -(tid & 7) * 8;     // past the tail: re-read the row start (discarded)
+        ok_ = c < C;
+        const int cc = ok_ ? c0 : -(tid & 7) * 8;    // past the tail: re-read the row start (zeroed in commit)
 #pragma unroll
-        for (int it = 0; it < N; ++it) v[it] = sel4(ok, *(const uint4*)(ptr[it] + cc));
+        for (int it = 0; it < N; ++it) v[it] = *(const uint4*)(ptr[it] + cc);
     }
     __device__ __forceinline__ void commit(const FOp&, uint32_t* lds, int tid)
     {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
             const int q = tid + NT * it;
-            *(uint4*)(lds + (q >> 3) * PP + (q & 7) * 4) = v[it];
+            *(uint4*)(lds + (q & 7) * T::BW + T::slot(q >> 3) * 4) = sel4(ok_, v[it]);
         }
     }
 };
 
-// Format P, kept list on the contraction (contiguous) axis: word (row, cp) holds
-// elements S[c0+2cp], S[c0+2cp+1] of the row, each cut out of its aligned dword.
+// Contraction axis contiguous in memory with the kept list on it: word (row, cp)
+// holds elements S[c0+2cp], S[c0+2cp+1] of the row, each cut out of its aligned
+// dword with one byte permute.
 template <int R, int NT>
 struct LdPG {
+    typedef Tile<R> T;
     static constexpr int N = R * 32 / NT;
     static constexpr int RSTEP = NT / 32;
-    static constexpr int WORDS = R * PP;
     static constexpr bool NEEDS_IDX = false;
     const E* rp;            // first row of this thread
     int64_t rstride;        // RSTEP rows, in elements
@@ -184,39 +205,45 @@ struct LdPG {
     }
     __device__ __forceinline__ void commit(const FOp&, uint32_t* lds, int tid)
     {
+        const int cp = tid & 31;
+        uint32_t* dst = lds + (cp >> 2) * T::BW + (cp & 3);
 #pragma unroll
         for (int it = 0; it < N; ++it)
-            lds[((tid >> 5) + RSTEP * it) * PP + (tid & 31)] = __builtin_amdgcn_perm(d1[it], d0[it], sel);
+            dst[T::slot((tid >> 5) + RSTEP * it) * 4] = __builtin_amdgcn_perm(d1[it], d0[it], sel);
     }
 };
 
-// Format Q, 16-byte loads of rows c and c+1, interleaved; optional row list on c.
+// Contraction axis strided in memory: a unit is 4 memory rows (c..c+3) x 8
+// consecutive columns, interleaved in registers; optional row list on c.
 template <int R, int NT>
 struct LdQV {
-    static constexpr int PQ = R + 8;
+    typedef Tile<R> T;
     static constexpr int UPR = R / 8;
-    static constexpr int N = BKD * UPR / NT;
-    static constexpr int WORDS = BKD * PQ;
+    static constexpr int N = 16 * UPR / NT;
     static constexpr bool NEEDS_IDX = false;
+    static_assert((16 * UPR) % NT == 0 && N >= 1, "unit count must divide over the threads");
     const E* colp[N];       // base + clamped column of the unit
-    int ra[N], rb[N];       // memory rows of the NEXT fetch
-    uint4 lo[N], hi[N];
+    int rr[N][4];           // memory rows of the NEXT fetch
+    uint4 v[N][4];
+    int left_[N];           // contraction indices left from the unit's first row (<= 0: all past the tail)
 
     __device__ __forceinline__ void rows_for(const FOp& op, int c0, int C, int tid)
     {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
-            const int c = c0 + 2 * ((tid + NT * it) / UPR);
-            const int ca = min(c, C - 1), cb = min(c + 1, C - 1);
-            ra[it] = op.map_s ? clamp_idx(op.map_s[ca], op.n_s) : ca;
-            rb[it] = op.map_s ? clamp_idx(op.map_s[cb], op.n_s) : cb;
+            const int c = c0 + 4 * ((tid + NT * it) / UPR);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int cu = min(c + u, C - 1);
+                rr[it][u] = op.map_s ? clamp_idx(op.map_s[cu], op.n_s) : cu;
+            }
         }
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
-            const int j = min(r0 + ((tid + NT * it) % UPR) * 8, rlim - 8);   // J is a multiple of 8 here
+            const int j = min(r0 + ((tid + NT * it) % UPR) * 8, rlim - 8);   // extent is a multiple of 8 here
             colp[it] = op.base + j;
         }
         rows_for(op, 0, C, tid);
@@ -225,9 +252,10 @@ struct LdQV {
     {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
-            const int c = c0 + 2 * ((tid + NT * it) / UPR);
-            lo[it] = sel4(c < C, *(const uint4*)(colp[it] + (size_t)ra[it] * (size_t)op.ld));
-            hi[it] = sel4(c + 1 < C, *(const uint4*)(colp[it] + (size_t)rb[it] * (size_t)op.ld));
+            left_[it] = C - (c0 + 4 * ((tid + NT * it) / UPR));
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[it][u] = *(const uint4*)(colp[it] + (size_t)rr[it][u] * (size_t)op.ld);
         }
         rows_for(op, c0 + BK, C, tid);
     }
@@ -236,143 +264,140 @@ struct LdQV {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
             const int q = tid + NT * it;
-            uint32_t w[8];
-            interleave8(lo[it], hi[it], w);
-            uint32_t* dst = lds + (q / UPR) * PQ + (q % UPR) * 8;
-            *(uint4*)dst = make_uint4(w[0], w[1], w[2], w[3]);
-            *(uint4*)(dst + 4) = make_uint4(w[4], w[5], w[6], w[7]);
+            const int kq = q / UPR, jc = q % UPR;
+            uint2 w[8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[it][u] = sel4(u < left_[it], v[it][u]);
+            interleave4x8(v[it], w);
+            uint32_t* dst = lds + (kq >> 1) * T::BW + (kq & 1) * 2 + jc * 36;  // slot(8 jc + m) = 9 jc + m
+#pragma unroll
+            for (int m = 0; m < 8; ++m) *(uint2*)(dst + m * 4) = w[m];
         }
     }
 };
 
-// Format Q with the kept list on the contiguous (non-contraction) axis: the
-// tile's R kept columns [r0, r0+cnt) of the list span the original columns
-// [S[r0], S[r0+cnt-1]]; that span is fetched in aligned chunks of 8 columns and
-// compacted on the way into LDS.  Units (kd, chunk) beyond SLOTS*NT per tile
-// (very sparse kept sets) are processed unpipelined in commit().
+// Contraction axis strided, kept list on the contiguous (non-contraction) axis:
+// the tile's kept columns [r0, r0+cnt) of the list span the original columns
+// [S[r0], S[r0+cnt-1]]; that span is fetched in aligned chunks of 8 columns
+// (units of 4 memory rows x 8 columns) and only the kept columns are written
+// to LDS, at their compacted rows.  Units beyond SLOTS*NT per tile (very sparse
+// kept sets) are processed unpipelined in commit().
 template <int R, int NT>
 struct LdQG {
-    static constexpr int PQ = R + 8;
-    static constexpr int WORDS = BKD * PQ;
-    static constexpr int SLOTS = 4;
+    typedef Tile<R> T;
+    static constexpr int SLOTS = 2;
     static constexpr bool NEEDS_IDX = true;
     const int* sidx;        // LDS copy of the tile's slice of the kept list
-    int cnt, pa, nch, nunits, c0_;
+    int cnt, pa, nch, nunits, c0_, c_lim;
     const E* colp[SLOTS];
-    uint32_t posa[SLOTS], posb[SLOTS];   // 8 compacted positions, one byte each
-    uint32_t meta[SLOTS];                // keep mask (bits 0-7) | kd << 8
-    uint4 lo[SLOTS], hi[SLOTS];
+    uint32_t off[SLOTS][4]; // LDS word offsets (slot * 4) of the 8 columns, 16 bits each
+    uint32_t meta[SLOTS];   // keep mask (bits 0-7) | kq << 8
+    uint4 v[SLOTS][4];
 
-    __device__ __forceinline__ void describe(const FOp& op, int q, const E*& cp, uint32_t& pa_, uint32_t& pb_, uint32_t& mt)
+    __device__ __forceinline__ void describe(const FOp& op, int q, const E*& cp, uint32_t o[4], uint32_t& mt)
     {
-        const int kd = q / nch;
-        const int p = pa + 8 * (q - kd * nch);
+        const int kq = q / nch;
+        const int p = pa + 8 * (q - kq * nch);
         int r = lower_bound_lds(sidx, cnt, p);
-        uint32_t mask = 0, a = 0, b = 0;
+        uint32_t mask = 0;
+        o[0] = o[1] = o[2] = o[3] = 0;
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             const bool kept = r < cnt && sidx[r] == p + m;
             if (kept) {
                 mask |= 1u << m;
-                if (m < 4) a |= (uint32_t)r << (8 * m); else b |= (uint32_t)r << (8 * (m - 4));
+                o[m >> 1] |= (uint32_t)(T::slot(r) * 4) << (16 * (m & 1));
                 ++r;
             }
         }
         cp = op.base + p;
-        pa_ = a; pb_ = b;
-        mt = mask | ((uint32_t)kd << 8);
+        mt = mask | ((uint32_t)kq << 8);
     }
-    __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int* idx_lds, int)
+    __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int* idx_lds, int C)
     {
         // idx_lds already holds clamp(S[r0 .. r0+cnt)) (filled by the kernel before init)
         sidx = idx_lds;
+        c_lim = C;
+        c0_ = 0;
         cnt = min(R, rlim - r0);
         pa = sidx[0] & ~7;
         nch = (sidx[cnt - 1] - pa) / 8 + 1;
-        nunits = BKD * nch;
+        nunits = 16 * nch;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int q = tid + NT * s;
             if (q < nunits) {
-                describe(op, q, colp[s], posa[s], posb[s], meta[s]);
+                describe(op, q, colp[s], off[s], meta[s]);
             } else {
-                colp[s] = op.base; posa[s] = posb[s] = 0; meta[s] = 0;     // nothing kept: no LDS write
+                colp[s] = op.base; meta[s] = 0;                      // nothing kept: no LDS write
+                off[s][0] = off[s][1] = off[s][2] = off[s][3] = 0;
             }
         }
+    }
+    static __device__ __forceinline__ void load4(const FOp& op, const E* cp, int c, int C, uint4 r[4])
+    {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            r[u] = *(const uint4*)(cp + (size_t)min(c + u, C - 1) * (size_t)op.ld);
     }
     __device__ __forceinline__ void fetch(const FOp& op, int c0, int C, int)
     {
         c0_ = c0;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            const int c = c0 + 2 * (int)(meta[s] >> 8);
-            const int ca = min(c, C - 1), cb = min(c + 1, C - 1);
-            lo[s] = sel4(c < C, *(const uint4*)(colp[s] + (size_t)ca * (size_t)op.ld));
-            hi[s] = sel4(c + 1 < C, *(const uint4*)(colp[s] + (size_t)cb * (size_t)op.ld));
-        }
+        for (int s = 0; s < SLOTS; ++s) load4(op, colp[s], c0 + 4 * (int)(meta[s] >> 8), C, v[s]);
     }
-    static __device__ __forceinline__ void scatter(uint32_t* lds, const uint4& l, const uint4& h,
-                                                   uint32_t pa_, uint32_t pb_, uint32_t mt)
+    // left: contraction indices left from the unit's first row; rows past the tail become zero
+    static __device__ __forceinline__ void scatter(uint32_t* lds, const uint4 r[4], const uint32_t o[4], uint32_t mt, int left)
     {
-        uint32_t w[8];
-        interleave8(l, h, w);
-        uint32_t* row = lds + (mt >> 8) * PQ;
+        uint2 w[8];
+        uint4 z[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) z[u] = sel4(u < left, r[u]);
+        interleave4x8(z, w);
+        const int kq = (int)(mt >> 8);
+        uint32_t* dst = lds + (kq >> 1) * T::BW + (kq & 1) * 2;
 #pragma unroll
         for (int m = 0; m < 8; ++m)
-            if (mt & (1u << m)) row[((m < 4 ? pa_ : pb_) >> (8 * (m & 3))) & 0xffu] = w[m];
+            if (mt & (1u << m)) *(uint2*)(dst + ((o[m >> 1] >> (16 * (m & 1))) & 0xffffu)) = w[m];
     }
     __device__ __forceinline__ void commit(const FOp& op, uint32_t* lds, int tid)
     {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) scatter(lds, lo[s], hi[s], posa[s], posb[s], meta[s]);
-        // units that did not fit the register slots
-        for (int q = tid + NT * SLOTS; q < nunits; q += NT) {
-            const E* cp; uint32_t a, b, mt;
-            describe(op, q, cp, a, b, mt);
-            const int c = c0_ + 2 * (int)(mt >> 8);
-            const int C = c_lim;
-            const int ca = min(c, C - 1), cb = min(c + 1, C - 1);
-            const uint4 l = sel4(c < C, *(const uint4*)(cp + (size_t)ca * (size_t)op.ld));
-            const uint4 h = sel4(c + 1 < C, *(const uint4*)(cp + (size_t)cb * (size_t)op.ld));
-            scatter(lds, l, h, a, b, mt);
+        for (int s = 0; s < SLOTS; ++s) scatter(lds, v[s], off[s], meta[s], c_lim - (c0_ + 4 * (int)(meta[s] >> 8)));
+        for (int q = tid + NT * SLOTS; q < nunits; q += NT) {     // units that did not fit the slots
+            const E* cp; uint32_t o[4], mt;
+            describe(op, q, cp, o, mt);
+            uint4 r[4];
+            const int c = c0_ + 4 * (int)(mt >> 8);
+            load4(op, cp, c, c_lim, r);
+            scatter(lds, r, o, mt, c_lim - c);
         }
     }
-    int c_lim;
 };
 
 // ---------------------------------------------------------------------------
-template <bool CC, int R>
-__device__ __forceinline__ bf16x8 read_frag(const uint32_t* lds, int row, int kd)
+__device__ __forceinline__ bf16x8 read_frag(const uint32_t* p)
 {
     union { uint4 u; bf16x8 b; } x;
-    if constexpr (CC) {
-        x.u = *(const uint4*)(lds + row * PP + kd);
-    } else {
-        constexpr int PQ = R + 8;
-        x.u = make_uint4(lds[kd * PQ + row], lds[(kd + 1) * PQ + row],
-                         lds[(kd + 2) * PQ + row], lds[(kd + 3) * PQ + row]);
-    }
+    x.u = *(const uint4*)p;
     return x.b;
 }
 
 template <int BM, int BN>
 constexpr int fast_smem_bytes()
 {
-    constexpr int a_words = BM * PP > BKD * (BM + 8) ? BM * PP : BKD * (BM + 8);
-    constexpr int b_words = BN * PP > BKD * (BN + 8) ? BN * PP : BKD * (BN + 8);
-    constexpr int stage_bytes = 2 * (a_words + b_words) * 4;
+    constexpr int stage_bytes = 2 * (Tile<BM>::WORDS + Tile<BN>::WORDS) * 4;
     constexpr int c_bytes = BM * (BN + 8) * 2;
     return (stage_bytes > c_bytes ? stage_bytes : c_bytes) + (BM + BN) * 4;
 }
 
-template <template <int, int> class LA_, template <int, int> class LB_, bool ACC, bool BCC,
-          int BM, int BN, int WM, int WN>
+template <template <int, int> class LA_, template <int, int> class LB_, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
-    constexpr int A_WORDS = BM * PP > BKD * (BM + 8) ? BM * PP : BKD * (BM + 8);
-    constexpr int B_WORDS = BN * PP > BKD * (BN + 8) ? BN * PP : BKD * (BN + 8);
+    constexpr int A_WORDS = Tile<BM>::WORDS;
+    constexpr int B_WORDS = Tile<BN>::WORDS;
     constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
     constexpr int CP = BN + 8;
     constexpr int IDX_OFF = (fast_smem_bytes<BM, BN>() - (BM + BN) * 4) / 4;
@@ -390,14 +415,17 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int grp = lane >> 5;
     const int wr0 = (wave / WN) * (BM / WM);
     const int wc0 = (wave % WN) * (BN / WN);
+    // word offset of this lane's first fragment row inside a block; the row 32
+    // further down sits 36 slots (144 words) further
+    const int arow = Tile<BM>::slot(wr0 + l32) * 4;
+    const int brow = Tile<BN>::slot(wc0 + l32) * 4;
 
     // Workgroups go round-robin to the 8 XCDs (each with its own L2): give every
     // XCD a contiguous range of tiles, ordered in groups of 4 tile-rows so that
     // the tiles running together share A rows and B columns.
-    const int nb = gridDim.x;
-    const int per = (nb + 7) / 8;
-    int t = (blockIdx.x % 8) * per + blockIdx.x / 8;
-    if (t >= nb) return;                       // cannot happen when nb % 8 == 0; host pads the grid
+    const int nb = gridDim.x;                  // a multiple of 8 (the host pads the grid)
+    const int per = nb / 8;
+    const int t = (blockIdx.x % 8) * per + blockIdx.x / 8;
     const int total = g.tiles_i * g.tiles_j;
     if (t >= total) return;
     constexpr int GI = 4;
@@ -432,43 +460,54 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     LB lb;
     la.init(g.A, i0, g.I, tid, idxA, g.C);
     lb.init(g.B, j0, g.J, tid, idxB, g.C);
-    if constexpr (LA::NEEDS_IDX) la.c_lim = g.C;
-    if constexpr (LB::NEEDS_IDX) lb.c_lim = g.C;
 
+    // Software pipeline over the contraction tiles: tile k is multiplied out of
+    // LDS stage k&1 while tile k+1 (fetched into registers one iteration
+    // earlier) is written to the other stage and the global loads of tile k+2
+    // are issued, both in the middle of the MFMA sequence.
     const int KT = (g.C + BK - 1) / BK;
     la.fetch(g.A, 0, g.C, tid);
     lb.fetch(g.B, 0, g.C, tid);
     la.commit(g.A, smem, tid);
     lb.commit(g.B, smem + A_WORDS, tid);
+    if (KT > 1) {
+        la.fetch(g.A, BK, g.C, tid);
+        lb.fetch(g.B, BK, g.C, tid);
+    }
     __syncthreads();
+
+    auto mma_step = [&](const uint32_t* as, const uint32_t* bs, int step) {
+        // lanes 0-31 take contraction indices 16*step .. +7, lanes 32-63 the next 8
+        const uint32_t* ab = as + (2 * step + grp) * Tile<BM>::BW;
+        const uint32_t* bb = bs + (2 * step + grp) * Tile<BN>::BW;
+        bf16x8 af[TM], bf[TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) af[a] = read_frag(ab + a * 144);
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bf[b] = read_frag(bb + b * 144);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+    };
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            la.fetch(g.A, (kt + 1) * BK, g.C, tid);
-            lb.fetch(g.B, (kt + 1) * BK, g.C, tid);
-        }
-        const uint32_t* as = smem + cur * STAGE_WORDS;
-        const uint32_t* bs = as + A_WORDS;
-#pragma unroll
-        for (int step = 0; step < BKD / 8; ++step) {
-            const int kd = step * 8 + grp * 4;
-            bf16x8 af[TM], bf[TN];
-#pragma unroll
-            for (int a = 0; a < TM; ++a) af[a] = read_frag<ACC, BM>(as, wr0 + a * 32 + l32, kd);
-#pragma unroll
-            for (int b = 0; b < TN; ++b) bf[b] = read_frag<BCC, BN>(bs, wc0 + b * 32 + l32, kd);
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int b = 0; b < TN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
-        }
-        if (more) {
+        const uint32_t* as = smem + cur * STAGE_WORDS + arow;
+        const uint32_t* bs = smem + cur * STAGE_WORDS + A_WORDS + brow;
+        mma_step(as, bs, 0);
+        mma_step(as, bs, 1);
+        if (kt + 1 < KT) {
             la.commit(g.A, smem + (cur ^ 1) * STAGE_WORDS, tid);
             lb.commit(g.B, smem + (cur ^ 1) * STAGE_WORDS + A_WORDS, tid);
         }
+        if (kt + 2 < KT) {
+            la.fetch(g.A, (kt + 2) * BK, g.C, tid);
+            lb.fetch(g.B, (kt + 2) * BK, g.C, tid);
+        }
+        mma_step(as, bs, 2);
+        mma_step(as, bs, 3);
         __syncthreads();
     }
 
@@ -549,12 +588,11 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
-template <template <int, int> class LA, template <int, int> class LB, bool ACC, bool BCC,
-          int BM, int BN, int WM, int WN>
+template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
 int launch_tile(const FArgs& a, hipStream_t stream)
 {
     constexpr int smem = fast_smem_bytes<BM, BN>();
-    auto fn = fast_kernel<LA, LB, ACC, BCC, BM, BN, WM, WN>;
+    auto fn = fast_kernel<LA, LB, BM, BN, WM, WN>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -571,13 +609,13 @@ int launch_tile(const FArgs& a, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
-template <template <int, int> class LA, template <int, int> class LB, bool ACC, bool BCC>
+template <template <int, int> class LA, template <int, int> class LB>
 int launch_shape(const FArgs& a, hipStream_t stream)
 {
     // tile choice: the largest tile whose grid still fills the 256 CUs reasonably
     const int64_t t256 = (int64_t)((a.I + 255) / 256) * ((a.J + 255) / 256);
-    if (t256 >= 200) return launch_tile<LA, LB, ACC, BCC, 256, 256, 2, 4>(a, stream);
-    return launch_tile<LA, LB, ACC, BCC, 128, 128, 2, 2>(a, stream);
+    if (t256 >= 200) return launch_tile<LA, LB, 256, 256, 2, 4>(a, stream);
+    return launch_tile<LA, LB, 128, 128, 2, 2>(a, stream);
 }
 
 }  // namespace
@@ -610,20 +648,20 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     a.tiles_i = a.tiles_j = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;
     if (d.A.c_contig && !d.B.c_contig) {            // forward: A format P, B format Q
-        if (!ag && !bg) return launch_shape<LdPV, LdQV, true, false>(a, stream);
-        if (ag && !bg) return launch_shape<LdPG, LdQV, true, false>(a, stream);
-        if (!ag && bg) return launch_shape<LdPV, LdQG, true, false>(a, stream);
+        if (!ag && !bg) return launch_shape<LdPV, LdQV>(a, stream);
+        if (ag && !bg) return launch_shape<LdPG, LdQV>(a, stream);
+        if (!ag && bg) return launch_shape<LdPV, LdQG>(a, stream);
         return -1;
     }
     if (d.A.c_contig && d.B.c_contig) {             // dX: both format P
-        if (!ag && !bg) return launch_shape<LdPV, LdPV, true, true>(a, stream);
-        if (ag && bg) return launch_shape<LdPG, LdPG, true, true>(a, stream);
+        if (!ag && !bg) return launch_shape<LdPV, LdPV>(a, stream);
+        if (ag && bg) return launch_shape<LdPG, LdPG>(a, stream);
         return -1;
     }
     if (!d.A.c_contig && !d.B.c_contig) {           // dW: both format Q
-        if (!ag && !bg) return launch_shape<LdQV, LdQV, false, false>(a, stream);
-        if (ag && !bg) return launch_shape<LdQG, LdQV, false, false>(a, stream);
-        if (!ag && bg) return launch_shape<LdQV, LdQG, false, false>(a, stream);
+        if (!ag && !bg) return launch_shape<LdQV, LdQV>(a, stream);
+        if (ag && !bg) return launch_shape<LdQG, LdQV>(a, stream);
+        if (!ag && bg) return launch_shape<LdQV, LdQG>(a, stream);
         return -1;
     }
     return -1;
