@@ -94,6 +94,17 @@ int64_t zr_keep_count(int64_t n, double ratio);
 int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio,
                      int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, void* stream);
 
+/* Size of the optional scratch buffer of the forward / backward calls below.
+ * With a DEVICE buffer of at least this many bytes (16-byte aligned) the calls
+ * first extract the kept columns of the ACTIVATION they gather along its
+ * contiguous axis (X[:,S] for DROP_K, dY[:,S] for DROP_N: the paper's
+ * "pruned_input", Sec. 3.1) into it, [M x n_keep rounded up to 64] bf16, zero
+ * padded, and then run the products on ordinary loads; the weight shard is never
+ * copied.  Without it (NULL, or too small) every gather is done in flight by
+ * the GEMM loaders; results are the same to the last bit either way.  Returns 0
+ * when no call would use a workspace (fp32).  Pure host function. */
+size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
+
 /* Forward of the resized linear layer (Sec. 3.1, forward paragraph).
  *  DROP_K: Y = X[:,S] W[S,:]            (full shape, nothing to impute)
  *  DROP_N: Y[:,S] = X W[:,S];  Y[:,P] imputed by `policy`
@@ -102,12 +113,16 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
  *  prev_Y: previous iteration's Y [M x N] with leading dimension ldy, needed for
  *  ZR_IMPUTE_SAME in DROP_N only (may alias Y: dropped positions then stay as
  *  they are); ignored otherwise.
- *  Launches: 1 for ZERO; 2 for AVERAGE / SAME (GEMM, then the imputation pass).
+ *  workspace / workspace_bytes: optional scratch, see zr_workspace_bytes; its
+ *  contents are undefined afterwards; calls that share one must be ordered on
+ *  one stream.
+ *  Launches: 1 for ZERO (+1 with a workspace in DROP_K); +1 for AVERAGE / SAME.
  *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE, POLICY, LIMIT, HIP. */
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy, const void* prev_Y, void* stream);
+                          int mode, int dtype, int policy, const void* prev_Y,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of the resized linear layer (Sec. 3.1, backward paragraph; the
  * upstream gradient is never pruned in the paper's DROP_K case).
@@ -115,7 +130,7 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
  *  DROP_N: dX = dY[:,S] W[:,S]^T (full shape);      dW[:,S] = X^T dY[:,S], dW[:,P] imputed
  *  dX [M x K] lddx and dW [K x N] lddw are outputs; either may be NULL to skip
  *  that product.  prev_dX / prev_dW (same shapes and leading dimensions as dX /
- *  dW) are read for ZR_IMPUTE_SAME only.
+ *  dW) are read for ZR_IMPUTE_SAME only.  workspace: as for the forward call.
  *  Errors as for the forward call. */
 int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           const void* dY, int64_t lddy,
@@ -123,7 +138,8 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
                           int mode, int dtype, int policy,
-                          const void* prev_dX, const void* prev_dW, void* stream);
+                          const void* prev_dX, const void* prev_dW,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* Stand-alone recovery/imputation (Sec. 3.1, "Our solution is to add missing
  * dimensions" and the three policies): fills every slice of out[rows x cols]

@@ -34,12 +34,43 @@ Operand operand(const void* base, int64_t ld, bool c_contig, const int32_t* map_
     o.base = base; o.ld = ld; o.c_contig = c_contig;
     o.map_strided = map_strided; o.map_contig = map_contig;
     o.n_strided = n_strided; o.n_contig = n_contig;
+    o.zero_padded = false;
     return o;
+}
+
+// Extracted activation in the caller's workspace: [M x width] bf16, width = n_keep
+// rounded up to 64, zero beyond n_keep.  Returns false when the workspace path
+// does not apply (then the GEMM loaders gather in flight).
+struct Extract {
+    bool use;
+    int width;
+};
+
+int round_up64(int v) { return (v + 63) / 64 * 64; }
+
+Extract plan_extract(const void* src, int64_t ld, int32_t M, int32_t n, int32_t n_keep, int dtype,
+                     const void* workspace, size_t workspace_bytes)
+{
+    Extract e{false, 0};
+    if (dtype != ZR_BF16 || !workspace || n_keep == n) return e;
+    const int width = round_up64(n_keep);
+    if ((size_t)M * (size_t)width * 2 > workspace_bytes) return e;
+    if ((uintptr_t)workspace % 16 != 0 || (uintptr_t)src % 4 != 0 || ld % 2 != 0 || n % 2 != 0) return e;
+    e.use = true;
+    e.width = width;
+    return e;
 }
 
 }  // namespace
 
 extern "C" {
+
+size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype)
+{
+    (void)K; (void)N; (void)mode;
+    if (dtype != ZR_BF16 || M < 1 || n_keep < 1) return 0;
+    return (size_t)M * (size_t)round_up64(n_keep) * 2;
+}
 
 const char* zr_status_string(int status)
 {
@@ -83,7 +114,8 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy, const void* prev_Y, void* stream)
+                          int mode, int dtype, int policy, const void* prev_Y,
+                          void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!X || !W || !Y) return ZR_ERR_NULL;
     int st = check_common(M, K, N, keep_idx, n_keep, mode, dtype, policy);
@@ -100,7 +132,15 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     d.out = Y; d.ldo = ldy; d.keep_idx = S; d.I = M;
     if (mode == ZR_DROP_K) {
         // Y[m,j] = sum_{c<n'} X[m,S[c]] * W[S[c],j]
-        d.A = operand(X, ldx, true, nullptr, S, M, K);
+        const Extract ex = plan_extract(X, ldx, M, K, n_keep, dtype, workspace, workspace_bytes);
+        if (ex.use) {
+            st = launch_compact_cols(X, ldx, M, K, keep_idx, n_keep, workspace, ex.width, ex.width, s);
+            if (st != ZR_OK) return st;
+            d.A = operand(workspace, ex.width, true, nullptr, nullptr, M, ex.width);
+            d.A.zero_padded = true;
+        } else {
+            d.A = operand(X, ldx, true, nullptr, S, M, K);
+        }
         d.B = operand(W, ldw, false, S, nullptr, K, N);
         d.J = N; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = N;
         return launch_gemm(d, s);
@@ -120,7 +160,8 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
                           int mode, int dtype, int policy,
-                          const void* prev_dX, const void* prev_dW, void* stream)
+                          const void* prev_dX, const void* prev_dW,
+                          void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!dY || (!dX && !dW)) return ZR_ERR_NULL;
     if ((dX && !W) || (dW && !X)) return ZR_ERR_NULL;
@@ -138,6 +179,17 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     const int32_t* S = full ? nullptr : keep_idx;
     const bool post = !full && policy != ZR_IMPUTE_ZERO;
 
+    // one extraction serves both products: X[:,S] (DROP_K, used by dW) or dY[:,S] (DROP_N)
+    Extract ex{false, 0};
+    if (mode == ZR_DROP_K) {
+        if (dW) ex = plan_extract(X, ldx, M, K, n_keep, dtype, workspace, workspace_bytes);
+        if (ex.use) st = launch_compact_cols(X, ldx, M, K, keep_idx, n_keep, workspace, ex.width, ex.width, s);
+    } else {
+        ex = plan_extract(dY, lddy, M, N, n_keep, dtype, workspace, workspace_bytes);
+        if (ex.use) st = launch_compact_cols(dY, lddy, M, N, keep_idx, n_keep, workspace, ex.width, ex.width, s);
+    }
+    if (st != ZR_OK) return st;
+
     GemmDesc d;
     d.dtype = dtype;
     d.keep_idx = S;
@@ -150,7 +202,12 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             d.J = n_keep; d.C = N; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = K;
         } else {
             // dX[m,k] = sum_{c<n'} dY[m,S[c]] * W[k,S[c]]
-            d.A = operand(dY, lddy, true, nullptr, S, M, N);
+            if (ex.use) {
+                d.A = operand(workspace, ex.width, true, nullptr, nullptr, M, ex.width);
+                d.A.zero_padded = true;
+            } else {
+                d.A = operand(dY, lddy, true, nullptr, S, M, N);
+            }
             d.B = operand(W, ldw, true, nullptr, S, K, N);
             d.J = K; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = K;
         }
@@ -165,13 +222,15 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
         d.out = dW; d.ldo = lddw; d.C = M;
         if (mode == ZR_DROP_K) {
             // dW[S[i],n] = sum_m X[m,S[i]] * dY[m,n], dropped rows imputed
-            d.A = operand(X, ldx, false, nullptr, S, M, K);
+            if (ex.use) d.A = operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width);
+            else d.A = operand(X, ldx, false, nullptr, S, M, K);
             d.B = operand(dY, lddy, false, nullptr, nullptr, M, N);
             d.I = n_keep; d.J = N; d.epilogue = full ? EPI_PLAIN : EPI_ROW_SCATTER; d.out_full = K;
         } else {
             // dW[k,S[j]] = sum_m X[m,k] * dY[m,S[j]], dropped columns imputed
             d.A = operand(X, ldx, false, nullptr, nullptr, M, K);
-            d.B = operand(dY, lddy, false, nullptr, S, M, N);
+            if (ex.use) d.B = operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width);
+            else d.B = operand(dY, lddy, false, nullptr, S, M, N);
             d.I = K; d.J = n_keep; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
         }
         st = launch_gemm(d, s);

@@ -47,7 +47,10 @@ struct Operand {
     const int32_t* map_strided;   // list applied to the strided axis, or nullptr
     const int32_t* map_contig;    // list applied to the contiguous axis, or nullptr
     int n_strided;                // full extent of the strided axis in memory (for clamping)
-    int n_contig;                 // full extent of the contiguous axis in memory
+    int n_contig;                 // readable extent of the contiguous axis in memory
+    // the tensor holds real zeros from the end of its logical extent up to the next
+    // multiple of 64 along the contiguous axis (extracted activations in the workspace)
+    bool zero_padded;
 };
 
 enum Epilogue { EPI_PLAIN = 0, EPI_COL_SCATTER = 1, EPI_ROW_SCATTER = 2 };
@@ -70,6 +73,8 @@ int launch_select(const float* scores, int n, int batch, int n_keep,
 int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
                   const int32_t* keep_idx, int n_keep, int policy, const void* prev,
                   int dtype, hipStream_t stream);
+int launch_compact_cols(const void* in, int64_t ld, int rows, int n, const int32_t* keep, int n_keep,
+                        void* out, int64_t ldo, int width, hipStream_t stream);
 int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? ZR_OK : ZR_ERR_HIP; }

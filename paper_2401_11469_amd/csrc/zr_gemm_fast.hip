@@ -48,6 +48,33 @@ template <int R> struct Tile {
     static __device__ __forceinline__ int slot(int i) { return i + (i >> 3); }
 };
 
+typedef __attribute__((address_space(3))) void* lds_void;
+typedef const __attribute__((address_space(1))) void* glb_void;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 u)
+{
+    union { uint4 u; bf16x8 b; } x;
+    x.u = u;
+    return x.b;
+}
+
+// Fragment reader of the block/slot layout (register-staged loaders).
+// w0: first tile row of this wavefront; t: 32-row sub-tile; step: 16 contraction
+// indices; lanes 0-31 take the first 8 of them, lanes 32-63 the other 8.
+template <int R> struct SlotReader {
+    int off;
+    __device__ __forceinline__ void setup(int w0, int lane)
+    {
+        off = Tile<R>::slot(w0 + (lane & 31)) * 4 + (lane >> 5) * Tile<R>::BW;
+    }
+    __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
+    {
+        // 32 rows further = 36 slots = 144 words
+        return as_frag(*(const uint4*)(stage + off + 2 * step * Tile<R>::BW + t * 144));
+    }
+};
+
 struct FOp {
     const E* base;
     int64_t ld;
@@ -121,6 +148,9 @@ __device__ __forceinline__ void interleave4x8(const uint4 r[4], uint2 w[8])
 template <int R, int NT>
 struct LdPV {
     typedef Tile<R> T;
+    typedef SlotReader<R> Reader;
+    static constexpr bool DMA = false;
+    static constexpr int WORDS = Tile<R>::WORDS;
     static constexpr int N = R * 8 / NT;
     static constexpr bool NEEDS_IDX = false;
     const E* ptr[N];
@@ -137,10 +167,12 @@ struct LdPV {
             ptr[it] = op.base + (size_t)srow * (size_t)op.ld + (q & 7) * 8;
         }
     }
-    __device__ __forceinline__ void fetch(const FOp&, int c0, int C, int tid)
+    __device__ __forceinline__ void fetch(const FOp& op, int c0, int C, int tid)
     {
-        const int c = c0 + (tid & 7) * 8;            // C is a multiple of 8 on this path
-        ok_ = c < C;
+        const int c = c0 + (tid & 7) * 8;
+        // a chunk is used if it starts inside the contraction range; it is always
+        // whole inside the readable row (n_c is a multiple of 8, >= C)
+        ok_ = c < C && c + 8 <= op.n_c;
         const int cc = ok_ ? c0 : -(tid & 7) * 8;    // past the tail: re-read the row start (zeroed in commit)
 #pragma unroll
         for (int it = 0; it < N; ++it) v[it] = *(const uint4*)(ptr[it] + cc);
@@ -161,6 +193,9 @@ struct LdPV {
 template <int R, int NT>
 struct LdPG {
     typedef Tile<R> T;
+    typedef SlotReader<R> Reader;
+    static constexpr bool DMA = false;
+    static constexpr int WORDS = Tile<R>::WORDS;
     static constexpr int N = R * 32 / NT;
     static constexpr int RSTEP = NT / 32;
     static constexpr bool NEEDS_IDX = false;
@@ -218,6 +253,9 @@ struct LdPG {
 template <int R, int NT>
 struct LdQV {
     typedef Tile<R> T;
+    typedef SlotReader<R> Reader;
+    static constexpr bool DMA = false;
+    static constexpr int WORDS = Tile<R>::WORDS;
     static constexpr int UPR = R / 8;
     static constexpr int N = 16 * UPR / NT;
     static constexpr bool NEEDS_IDX = false;
@@ -243,7 +281,9 @@ struct LdQV {
     {
 #pragma unroll
         for (int it = 0; it < N; ++it) {
-            const int j = min(r0 + ((tid + NT * it) % UPR) * 8, rlim - 8);   // extent is a multiple of 8 here
+            // the readable row length n_c is a multiple of 8 (>= 8); columns past the
+            // operand's extent are clamped into it and only feed discarded results
+            const int j = min(r0 + ((tid + NT * it) % UPR) * 8, op.n_c - 8);
             colp[it] = op.base + j;
         }
         rows_for(op, 0, C, tid);
@@ -285,6 +325,9 @@ struct LdQV {
 template <int R, int NT>
 struct LdQG {
     typedef Tile<R> T;
+    typedef SlotReader<R> Reader;
+    static constexpr bool DMA = false;
+    static constexpr int WORDS = Tile<R>::WORDS;
     static constexpr int SLOTS = 2;
     static constexpr bool NEEDS_IDX = true;
     const int* sidx;        // LDS copy of the tile's slice of the kept list
@@ -376,19 +419,181 @@ struct LdQG {
 };
 
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8 read_frag(const uint32_t* p)
+// Direct-to-LDS loaders (global_load_lds_dwordx4): every lane names a 16-byte
+// global chunk and the 64 chunks of a wavefront land back to back in 1 KB of
+// LDS, so the layout is contiguous per instruction and bank conflicts are
+// avoided by permuting WHICH chunk a lane fetches (XOR swizzles), never by
+// padding.  No staging registers, no ds_write, and the L1 -> LDS path sustains
+// ~56 B/clk/CU where loads into registers give ~32.
+// A tile whose contraction extent is not a multiple of 64 re-reads valid data
+// past the tail; the host only pairs such a tile with an operand that zeroes
+// its own tail.
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
 {
-    union { uint4 u; bf16x8 b; } x;
-    x.u = *(const uint4*)p;
-    return x.b;
+    __builtin_amdgcn_global_load_lds((glb_void)gptr, (lds_void)lds_uniform, 16, 0, 0);
 }
 
-template <int BM, int BN>
+// Contraction axis contiguous in memory (optional row list): LDS row i holds
+// its 8 chunks at positions chunk ^ (i & 7).
+template <int R, int NT>
+struct DmaP {
+    static constexpr bool DMA = true;
+    static constexpr bool NEEDS_IDX = false;
+    static constexpr int WORDS = R * 32;
+    static constexpr int NW = NT / 64;
+    static constexpr int N = R / 8 / NW;         // instructions per wavefront per tile
+    const E* ptr[N];
+    int chunk_;                                   // first contraction index of this lane's chunk
+
+    struct Reader {
+        int off, x;
+        __device__ __forceinline__ void setup(int w0, int lane)
+        {
+            off = (w0 + (lane & 31)) * 32;
+            x = ((lane & 7) << 2) ^ ((lane >> 5) << 2);     // word offset of chunk (grp ^ (row & 7))
+        }
+        __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
+        {
+            return as_frag(*(const uint4*)(stage + off + t * 1024 + (x ^ (step << 3))));
+        }
+    };
+
+    __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int)
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+        chunk_ = ((lane & 7) ^ (lane >> 3)) * 8;
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int i = min(r0 + 8 * (wave + NW * q) + (lane >> 3), rlim - 1);
+            const int srow = op.map_s ? clamp_idx(op.map_s[i], op.n_s) : i;
+            ptr[q] = op.base + (size_t)srow * (size_t)op.ld;
+        }
+    }
+    __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
+    {
+        const int wave = tid >> 6;
+        const int c = min(c0 + chunk_, op.n_c - 8);              // the readable row length is a multiple of 8
+#pragma unroll
+        for (int q = 0; q < N; ++q) dma16(ptr[q] + c, stage + (wave + NW * q) * 256);
+    }
+};
+
+// Contraction axis strided in memory (optional row list on it): LDS keeps the
+// memory rows as they are (row c = R consecutive columns), with the 16-byte
+// chunk index XORed by 2 * (c & 3); fragments are read with the transposing
+// ds_read_tr16_b64, which hands a lane 4 consecutive c of ONE column out of a
+// 4 (c) x 16 (columns) block read by its 16-lane group.
+template <int R, int NT>
+struct DmaQ {
+    static constexpr bool DMA = true;
+    static constexpr bool NEEDS_IDX = false;
+    static constexpr int WORDS = BK * R / 2;
+    static constexpr int NW = NT / 64;
+    static constexpr int CPR = R / 8;            // chunks per row
+    static constexpr int RPI = 64 / CPR;         // rows per instruction
+    static constexpr int N = CPR / NW;           // instructions per wavefront per tile
+    static_assert(CPR % NW == 0 && N >= 1 && 64 % CPR == 0, "tile does not split over the wavefronts");
+    const E* colp[N];
+    int rr[N];                                    // memory row of the NEXT issue
+
+    struct Reader {
+        int rowbase, coloff[4];
+        __device__ __forceinline__ void setup(int w0, int lane)
+        {
+            const int t16 = lane & 15;
+            rowbase = (8 * (lane >> 5) + (t16 >> 2)) * (R / 2);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int col = w0 + t * 32 + 16 * ((lane >> 4) & 1) + 4 * (t16 & 3);
+                coloff[t] = (((col >> 3) ^ (2 * (t16 >> 2))) << 2) + ((col & 7) >> 1);
+            }
+        }
+        __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
+        {
+            typedef __attribute__((address_space(3))) v4i16* lp;
+            const uint32_t* p = stage + 16 * step * (R / 2) + rowbase + coloff[t];
+            union { v4i16 h[2]; bf16x8 b; } x;
+            x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
+            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (R / 2)));
+            return x.b;
+        }
+    };
+
+    __device__ __forceinline__ int tile_row(int q, int tid) const
+    {
+        return RPI * ((tid >> 6) + NW * q) + (tid & 63) / CPR;
+    }
+    __device__ __forceinline__ void rows_for(const FOp& op, int c0, int C, int tid)
+    {
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int c = min(c0 + tile_row(q, tid), C - 1);
+            rr[q] = op.map_s ? clamp_idx(op.map_s[c], op.n_s) : c;
+        }
+    }
+    __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
+    {
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int chunk = ((tid & 63) % CPR) ^ (2 * (tile_row(q, tid) & 3));
+            colp[q] = op.base + min(r0 + chunk * 8, op.n_c - 8);     // the readable row length is a multiple of 8
+        }
+        rows_for(op, 0, C, tid);
+    }
+    __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
+    {
+        const int wave = tid >> 6;
+#pragma unroll
+        for (int q = 0; q < N; ++q)
+            dma16(colp[q] + (size_t)rr[q] * (size_t)op.ld, stage + (wave + NW * q) * 256);
+        rows_for(op, c0 + BK, C, tid);
+    }
+};
+
+template <int AW, int BW_, int BM, int BN>
 constexpr int fast_smem_bytes()
 {
-    constexpr int stage_bytes = 2 * (Tile<BM>::WORDS + Tile<BN>::WORDS) * 4;
+    constexpr int stage_bytes = 2 * (AW + BW_) * 4;
     constexpr int c_bytes = BM * (BN + 8) * 2;
     return (stage_bytes > c_bytes ? stage_bytes : c_bytes) + (BM + BN) * 4;
+}
+
+// One iteration of the contraction pipeline.  `rd` (the stage being multiplied)
+// and `wr` (the stage being filled) never overlap; declaring that lets the
+// compiler keep the direct-to-LDS loads in flight across the fragment reads
+// instead of waiting for them before the first ds_read.
+template <class LA, class LB, int TM, int TN>
+__device__ __forceinline__ void pipeline_step(
+    LA& la, LB& lb, const typename LA::Reader& ra, const typename LB::Reader& rb,
+    const FArgs& g, const uint32_t* __restrict__ rd, uint32_t* __restrict__ wr,
+    int c_next, bool more, int tid, f32x16 (&acc)[TM][TN])
+{
+    constexpr int A_WORDS = LA::WORDS;
+    if (more) {
+        if constexpr (LA::DMA) la.issue(g.A, wr, c_next, g.C, tid); else la.fetch(g.A, c_next, g.C, tid);
+        if constexpr (LB::DMA) lb.issue(g.B, wr + A_WORDS, c_next, g.C, tid); else lb.fetch(g.B, c_next, g.C, tid);
+    }
+#pragma unroll
+    for (int step = 0; step < BK / 16; ++step) {
+        bf16x8 af[TM], bf[TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) af[a] = ra.read(rd, a, step);
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bf[b] = rb.read(rd + A_WORDS, b, step);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+    }
+    if (more) {
+        if constexpr (!LA::DMA) la.commit(g.A, wr, tid);
+        if constexpr (!LB::DMA) lb.commit(g.B, wr + A_WORDS, tid);
+        // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
+        if constexpr (LA::DMA || LB::DMA) __builtin_amdgcn_s_waitcnt(0x0f70);
+    }
 }
 
 template <template <int, int> class LA_, template <int, int> class LB_, int BM, int BN, int WM, int WN>
@@ -396,13 +601,13 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
-    constexpr int A_WORDS = Tile<BM>::WORDS;
-    constexpr int B_WORDS = Tile<BN>::WORDS;
-    constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
-    constexpr int CP = BN + 8;
-    constexpr int IDX_OFF = (fast_smem_bytes<BM, BN>() - (BM + BN) * 4) / 4;
     typedef LA_<BM, NT> LA;
     typedef LB_<BN, NT> LB;
+    constexpr int A_WORDS = LA::WORDS;
+    constexpr int B_WORDS = LB::WORDS;
+    constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
+    constexpr int CP = BN + 8;
+    constexpr int IDX_OFF = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN>() - (BM + BN) * 4) / 4;
 
     extern __shared__ __align__(16) uint32_t smem[];
     int* idxA = (int*)(smem + IDX_OFF);
@@ -415,10 +620,10 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int grp = lane >> 5;
     const int wr0 = (wave / WN) * (BM / WM);
     const int wc0 = (wave % WN) * (BN / WN);
-    // word offset of this lane's first fragment row inside a block; the row 32
-    // further down sits 36 slots (144 words) further
-    const int arow = Tile<BM>::slot(wr0 + l32) * 4;
-    const int brow = Tile<BN>::slot(wc0 + l32) * 4;
+    typename LA::Reader ra;
+    typename LB::Reader rb;
+    ra.setup(wr0, lane);
+    rb.setup(wc0, lane);
 
     // Workgroups go round-robin to the 8 XCDs (each with its own L2): give every
     // XCD a contiguous range of tiles, ordered in groups of 4 tile-rows so that
@@ -461,53 +666,29 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     la.init(g.A, i0, g.I, tid, idxA, g.C);
     lb.init(g.B, j0, g.J, tid, idxB, g.C);
 
-    // Software pipeline over the contraction tiles: tile k is multiplied out of
-    // LDS stage k&1 while tile k+1 (fetched into registers one iteration
-    // earlier) is written to the other stage and the global loads of tile k+2
-    // are issued, both in the middle of the MFMA sequence.
+    // Pipeline over the contraction tiles: while tile k is multiplied out of LDS
+    // stage k&1, tile k+1 travels: direct-to-LDS loaders write it straight into
+    // the other stage, register-staged loaders hold it in registers and write
+    // it at the end of the iteration.
     const int KT = (g.C + BK - 1) / BK;
-    la.fetch(g.A, 0, g.C, tid);
-    lb.fetch(g.B, 0, g.C, tid);
-    la.commit(g.A, smem, tid);
-    lb.commit(g.B, smem + A_WORDS, tid);
-    if (KT > 1) {
-        la.fetch(g.A, BK, g.C, tid);
-        lb.fetch(g.B, BK, g.C, tid);
-    }
-    __syncthreads();
-
-    auto mma_step = [&](const uint32_t* as, const uint32_t* bs, int step) {
-        // lanes 0-31 take contraction indices 16*step .. +7, lanes 32-63 the next 8
-        const uint32_t* ab = as + (2 * step + grp) * Tile<BM>::BW;
-        const uint32_t* bb = bs + (2 * step + grp) * Tile<BN>::BW;
-        bf16x8 af[TM], bf[TN];
-#pragma unroll
-        for (int a = 0; a < TM; ++a) af[a] = read_frag(ab + a * 144);
-#pragma unroll
-        for (int b = 0; b < TN; ++b) bf[b] = read_frag(bb + b * 144);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-            for (int b = 0; b < TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+    auto start_tile = [&](int kt, uint32_t* stage) {
+        if constexpr (LA::DMA) la.issue(g.A, stage, kt * BK, g.C, tid); else la.fetch(g.A, kt * BK, g.C, tid);
+        if constexpr (LB::DMA) lb.issue(g.B, stage + A_WORDS, kt * BK, g.C, tid); else lb.fetch(g.B, kt * BK, g.C, tid);
     };
+    auto finish_tile = [&](uint32_t* stage) {
+        if constexpr (!LA::DMA) la.commit(g.A, stage, tid);
+        if constexpr (!LB::DMA) lb.commit(g.B, stage + A_WORDS, tid);
+        // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
+        if constexpr (LA::DMA || LB::DMA) __builtin_amdgcn_s_waitcnt(0x0f70);
+    };
+    start_tile(0, smem);
+    finish_tile(smem);
+    __syncthreads();
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
-        const uint32_t* as = smem + cur * STAGE_WORDS + arow;
-        const uint32_t* bs = smem + cur * STAGE_WORDS + A_WORDS + brow;
-        mma_step(as, bs, 0);
-        mma_step(as, bs, 1);
-        if (kt + 1 < KT) {
-            la.commit(g.A, smem + (cur ^ 1) * STAGE_WORDS, tid);
-            lb.commit(g.B, smem + (cur ^ 1) * STAGE_WORDS + A_WORDS, tid);
-        }
-        if (kt + 2 < KT) {
-            la.fetch(g.A, (kt + 2) * BK, g.C, tid);
-            lb.fetch(g.B, (kt + 2) * BK, g.C, tid);
-        }
-        mma_step(as, bs, 2);
-        mma_step(as, bs, 3);
+        pipeline_step<LA, LB, TM, TN>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
+                                      (kt + 1) * BK, kt + 1 < KT, tid, acc);
         __syncthreads();
     }
 
@@ -591,7 +772,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
 int launch_tile(const FArgs& a, hipStream_t stream)
 {
-    constexpr int smem = fast_smem_bytes<BM, BN>();
+    constexpr int smem = fast_smem_bytes<LA<BM, 64 * WM * WN>::WORDS, LB<BN, 64 * WM * WN>::WORDS, BM, BN>();
     auto fn = fast_kernel<LA, LB, BM, BN, WM, WN>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -627,16 +808,15 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     if (d.dtype != ZR_BF16) return -1;
     auto aligned = [](const void* p, int64_t ld) { return ((uintptr_t)p % 16 == 0) && (ld % 8 == 0); };
     if (!aligned(d.A.base, d.A.ld) || !aligned(d.B.base, d.B.ld) || !aligned(d.out, d.ldo)) return -1;
-    // every extent that is walked in 8-element chunks must be a multiple of 8
-    auto chunked_ok = [](const Operand& o, int n_rows_canon, int C) {
-        if (o.c_contig) {
-            if (o.map_contig) return o.map_strided == nullptr && o.n_contig % 2 == 0;   // PG reads aligned dwords
-            return C % 8 == 0;                                           // PV: C is the memory row length
+    // every memory row that is walked in 16-byte chunks must be a multiple of 8 long
+    auto chunked_ok = [](const Operand& o) {
+        if (o.map_contig) {
+            if (o.map_strided) return false;
+            return o.c_contig ? o.n_contig % 2 == 0 : o.n_contig % 8 == 0;   // PG reads aligned dwords, QG chunks
         }
-        if (o.map_contig) return o.map_strided == nullptr && o.n_contig % 8 == 0;   // QG
-        return n_rows_canon % 8 == 0;                                    // QV: J (or I) is the memory row length
+        return o.n_contig % 8 == 0;
     };
-    if (!chunked_ok(d.A, d.I, d.C) || !chunked_ok(d.B, d.J, d.C)) return -1;
+    if (!chunked_ok(d.A) || !chunked_ok(d.B)) return -1;
     if (d.epilogue != EPI_COL_SCATTER && d.J % 8 != 0) return -1;
     if (d.I < 1 || d.J < 1 || d.C < 1) return -1;
 
@@ -647,21 +827,29 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     a.out = (E*)d.out; a.ldo = d.ldo; a.epilogue = d.epilogue; a.keep = d.keep_idx; a.out_full = d.out_full;
     a.tiles_i = a.tiles_j = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;
-    if (d.A.c_contig && !d.B.c_contig) {            // forward: A format P, B format Q
-        if (!ag && !bg) return launch_shape<LdPV, LdQV>(a, stream);
-        if (ag && !bg) return launch_shape<LdPG, LdQV>(a, stream);
-        if (!ag && bg) return launch_shape<LdPV, LdQG>(a, stream);
+    // Direct-to-LDS loaders cannot zero the contraction tail of the last tile
+    // themselves: either the tiles are full, or one operand supplies the zeros
+    // (a register-staged loader, or a zero-padded extracted activation).
+    const bool full_tiles = d.C % BK == 0;
+    const bool a_zero = ag || (d.A.c_contig && d.A.zero_padded);
+    const bool b_zero = bg || (d.B.c_contig && d.B.zero_padded);
+    const bool dma_ok = full_tiles || a_zero || b_zero;
+    if (d.A.c_contig && !d.B.c_contig) {            // forward: X rows, W columns
+        if (!ag && !bg) return dma_ok ? launch_shape<DmaP, DmaQ>(a, stream) : launch_shape<LdPV, LdQV>(a, stream);
+        if (ag && !bg) return launch_shape<LdPG, DmaQ>(a, stream);
+        if (!ag && bg) return launch_shape<DmaP, LdQG>(a, stream);
         return -1;
     }
-    if (d.A.c_contig && d.B.c_contig) {             // dX: both format P
-        if (!ag && !bg) return launch_shape<LdPV, LdPV>(a, stream);
+    if (d.A.c_contig && d.B.c_contig) {             // dX
+        if (!ag && !bg) return dma_ok ? launch_shape<DmaP, DmaP>(a, stream) : launch_shape<LdPV, LdPV>(a, stream);
         if (ag && bg) return launch_shape<LdPG, LdPG>(a, stream);
+        if (!ag && bg) return launch_shape<DmaP, LdPG>(a, stream);
         return -1;
     }
-    if (!d.A.c_contig && !d.B.c_contig) {           // dW: both format Q
-        if (!ag && !bg) return launch_shape<LdQV, LdQV>(a, stream);
-        if (ag && !bg) return launch_shape<LdQG, LdQV>(a, stream);
-        if (!ag && bg) return launch_shape<LdQV, LdQG>(a, stream);
+    if (!d.A.c_contig && !d.B.c_contig) {           // dW
+        if (!ag && !bg) return full_tiles ? launch_shape<DmaQ, DmaQ>(a, stream) : launch_shape<LdQV, LdQV>(a, stream);
+        if (ag && !bg) return launch_shape<LdQG, DmaQ>(a, stream);
+        if (!ag && bg) return launch_shape<DmaQ, LdQG>(a, stream);
         return -1;
     }
     return -1;

@@ -32,12 +32,16 @@ _lib.zr_keep_count.argtypes = [_i64, _f64]
 _lib.zr_keep_count.restype = _i64
 _lib.zr_resize_select.argtypes = [_vp, _i32, _i32, _f64, _vp, _vp, _i64, _vp]
 _lib.zr_resize_select.restype = ctypes.c_int
+_lib.zr_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int, ctypes.c_int]
+_lib.zr_workspace_bytes.restype = ctypes.c_size_t
 _lib.zr_resized_linear_fwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32,
-                                       _vp, _i32, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp]
+                                       _vp, _i32, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp,
+                                       _vp, ctypes.c_size_t, _vp]
 _lib.zr_resized_linear_fwd.restype = ctypes.c_int
 _lib.zr_resized_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                        _i32, _i32, _i32, _vp, _i32,
-                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
+                                       _vp, ctypes.c_size_t, _vp]
 _lib.zr_resized_linear_bwd.restype = ctypes.c_int
 _lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, ctypes.c_int, _vp]
 _lib.zr_impute.restype = ctypes.c_int
@@ -76,6 +80,19 @@ def _mat(t: Optional[torch.Tensor], name: str):
 def _stream(stream) -> int:
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+def workspace_bytes(M: int, K: int, N: int, n_keep: int, mode: int, dtype) -> int:
+    code = dtype if isinstance(dtype, int) else (BF16 if dtype == torch.bfloat16 else F32)
+    return int(_lib.zr_workspace_bytes(M, K, N, n_keep, mode, code))
+
+
+def _ws(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return None, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace: need a contiguous GPU tensor")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
 def keep_count(n: int, ratio: float) -> int:
@@ -121,7 +138,8 @@ def resize_select(scores: torch.Tensor, ratio: float, keep_idx: Optional[torch.T
 
 def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor, mode: int,
                        policy: int = ZERO, prev_Y: Optional[torch.Tensor] = None,
-                       Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                       Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                       stream=None) -> torch.Tensor:
     M, K = X.shape
     N = W.shape[1]
     if W.shape[0] != K or W.dtype != X.dtype:
@@ -134,7 +152,7 @@ def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor,
         raise ValueError("prev_Y must share Y's leading dimension")
     _check(_lib.zr_resized_linear_fwd(xp, ldx, wp, ldw, yp, ldy, M, K, N,
                                       keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
-                                      policy, pp, _stream(stream)))
+                                      policy, pp, *_ws(workspace), _stream(stream)))
     return Y
 
 
@@ -142,7 +160,7 @@ def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_
                        mode: int, policy: int = ZERO, prev_dX: Optional[torch.Tensor] = None,
                        prev_dW: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
                        dW: Optional[torch.Tensor] = None, need_dX: bool = True, need_dW: bool = True,
-                       stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
     M, K = X.shape
     N = W.shape[1]
     if dY.shape != (M, N):
@@ -158,7 +176,7 @@ def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_
         raise ValueError("previous tensors must share the outputs' leading dimensions")
     _check(_lib.zr_resized_linear_bwd(xp, ldx, wp, ldw, gp, ldg, dxp, lddx, dwp, lddw, M, K, N,
                                       keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
-                                      policy, pxp, pwp, _stream(stream)))
+                                      policy, pxp, pwp, *_ws(workspace), _stream(stream)))
     return (dX if need_dX else None), (dW if need_dW else None)
 
 

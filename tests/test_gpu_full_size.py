@@ -54,8 +54,10 @@ def _check_projection(zr, oracle, cid, pi, ratio):
     Y = torch.full((M, N), 3.0, dtype=tdt, device="cuda")
     dX = torch.full((M, K), 3.0, dtype=tdt, device="cuda")
     dW = torch.full((K, N), 3.0, dtype=tdt, device="cuda")
-    zr.resized_linear_fwd(X, W, keep, mode, Y=Y)
-    zr.resized_linear_bwd(X, W, dY, keep, mode, dX=dX, dW=dW)
+    # as bench.py launches it: with the optional scratch buffer
+    ws = torch.empty(max(16, zr.workspace_bytes(M, K, N, len(S), mode, tdt)), dtype=torch.uint8, device="cuda")
+    zr.resized_linear_fwd(X, W, keep, mode, Y=Y, workspace=ws)
+    zr.resized_linear_bwd(X, W, dY, keep, mode, dX=dX, dW=dW, workspace=ws)
     torch.cuda.synchronize()
 
     # (1) whole tensors: masked-dense identity with a library GEMM in fp32

@@ -165,10 +165,15 @@ def test_impute_parity(zr, torch_mod, oracle, dtype, axis, policy, rows, cols):
 
 # ------------------------------------------------------------------- GEMMs ---
 
-def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0):
-    """fwd + bwd through the C ABI; returns float64 numpy (Y, dX, dW)."""
+def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False):
+    """fwd + bwd through the C ABI; returns float64 numpy (Y, dX, dW).
+    use_ws: hand the calls the optional scratch buffer (extracted-activation path)."""
     M, K = case["X"].shape
     N = case["W"].shape[1]
+    ws = None
+    if use_ws:
+        nbytes = zr.workspace_bytes(M, K, N, len(S), mode, _tdtype(torch, dtype))
+        ws = torch.full((max(nbytes, 16),), 0x7F, dtype=torch.uint8, device="cuda")   # NaN-pattern garbage
     ld = (lambda c: c + pad) if pad else (lambda c: None)
     X = to_gpu(torch, case["X"], dtype, ld(K))
     W = to_gpu(torch, case["W"], dtype, ld(N))
@@ -180,8 +185,8 @@ def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0):
     Y = to_gpu(torch, np.full((M, N), 555.0, np.float32), dtype, ld(N))
     dX = to_gpu(torch, np.full((M, K), 555.0, np.float32), dtype, ld(K))
     dW = to_gpu(torch, np.full((K, N), 555.0, np.float32), dtype, ld(N))
-    zr.resized_linear_fwd(X, W, keep, mode, policy, pY, Y=Y)
-    zr.resized_linear_bwd(X, W, dY, keep, mode, policy, pdX, pdW, dX=dX, dW=dW)
+    zr.resized_linear_fwd(X, W, keep, mode, policy, pY, Y=Y, workspace=ws)
+    zr.resized_linear_bwd(X, W, dY, keep, mode, policy, pdX, pdW, dX=dX, dW=dW, workspace=ws)
     torch.cuda.synchronize()
     if pad:
         for t in (Y, dX, dW):
@@ -277,6 +282,28 @@ def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
             S = S.astype(np.int32)
             got = run_layer(zr, torch, case, S, mode, "bf16")
             check_layer(oracle, case, S, mode, "bf16", ZERO, got)
+
+
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("M,K,N", [(130, 200, 136), (257, 130, 300), (320, 520, 392), (64, 64, 64)])
+def test_workspace_path_matches_oracle_and_in_flight_path(zr, torch_mod, oracle, mode, M, K, N):
+    """With the optional scratch buffer the activations' kept columns are
+    extracted first; results must match the oracle and the in-flight path."""
+    torch = torch_mod
+    case = wl.random_case(31 + M + K + N, M, K, N, "bf16")
+    n = N if mode == DROP_N else K
+    for n_keep in sorted({1, 2, max(1, n // 2), max(1, (3 * n) // 4), n - 1}):
+        S = subset(n_keep * 7 + n, n, n_keep)
+        a = run_layer(zr, torch, case, S, mode, "bf16", use_ws=True)
+        check_layer(oracle, case, S, mode, "bf16", ZERO, a)
+        b = run_layer(zr, torch, case, S, mode, "bf16", use_ws=False)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    # other policies go through the same extraction
+    S = subset(5, n, (2 * n) // 3)
+    for policy in (AVERAGE, SAME):
+        got = run_layer(zr, torch, case, S, mode, "bf16", policy, use_ws=True)
+        check_layer(oracle, case, S, mode, "bf16", policy, got)
 
 
 def test_bitwise_repeatable(zr, torch_mod):
