@@ -26,22 +26,6 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 
 
-def kernel_label(op: str, mode: int, full: bool, dtype: str) -> str:
-    """Name of the gemm_kernel instantiation a product runs on, as rocprofv3
-    prints it: <dtype, A contraction-contiguous, A vector loads, B contraction-
-    contiguous, B vector loads, BM, BN>."""
-    dt = 1 if dtype == "bf16" else 0
-    fmt = {"fwd": (True, False), "dX": (True, True), "dW": (False, False)}[op]
-    if full:
-        vec = (True, True)
-    else:
-        vec = {("fwd", 1): (False, True), ("fwd", 0): (True, False),
-               ("dX", 1): (True, True), ("dX", 0): (False, False),
-               ("dW", 1): (False, True), ("dW", 0): (True, False)}[(op, mode)]
-    b = lambda v: "true" if v else "false"
-    return f"gemm_kernel<{dt}, {b(fmt[0])}, {b(vec[0])}, {b(fmt[1])}, {b(vec[1])}, 128, 128>"
-
-
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +68,9 @@ def main() -> int:
             keep=torch.empty((1, n), dtype=torch.int32, device=dev),
             drop=torch.empty((1, n), dtype=torch.int32, device=dev)))
         del t
+    # one scratch buffer shared by all calls (they are ordered on one stream)
+    ws_bytes = max(zr.workspace_bytes(M, p["pr"].K, p["pr"].N, p["n"], p["pr"].mode, tdt) for p in projs)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev) if ws_bytes else None
     torch.cuda.synchronize()
 
     def step_flops(ratio: float) -> float:
@@ -97,21 +84,34 @@ def main() -> int:
             keep, _ = zr.resize_select(p["scores"], r, keep_idx=p["keep"], drop_idx=p["drop"])
             full = keep.numel() == p["n"]
             if events is None:
-                zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"])
-                zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"])
+                zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
+                zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws)
             else:
+                # one event pair per product; a call that first extracts the kept
+                # activation columns into the scratch buffer (a second, HBM-bound
+                # kernel) is charged only the GEMM: the same extraction is timed
+                # on its own right before and subtracted
                 fl = 2.0 * M * pr.K * pr.N * keep.numel() / p["n"]
+                ev = lambda: torch.cuda.Event(enable_timing=True)
                 for op in ("fwd", "dX", "dW"):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    extracts = ws is not None and not full and (
+                        (pr.mode == zr.DROP_K and op in ("fwd", "dW")) or (pr.mode == zr.DROP_N and op in ("dX", "dW")))
+                    x0, x1, e0, e1 = ev(), ev(), ev(), ev()
+                    if extracts:
+                        src = p["X"] if pr.mode == zr.DROP_K else p["dY"]
+                        width = (keep.numel() + 63) // 64 * 64
+                        x0.record()
+                        zr.extract_kept_columns(src, keep, out=ws[:M * width * 2].view(tdt).view(M, width))
+                        x1.record()
                     e0.record()
                     if op == "fwd":
-                        zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"])
+                        zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
                     elif op == "dX":
-                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], need_dW=False)
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], need_dW=False, workspace=ws)
                     else:
-                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False)
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False, workspace=ws)
                     e1.record()
-                    events.append((kernel_label(op, pr.mode, full, cfg.dtype), fl, e0, e1))
+                    events.append((zr.debug_last_kernel(), fl, e0, e1, (x0, x1) if extracts else None))
 
     ratios = wl.ratio_sequence(args.config, args.warmup + args.steps)
 
@@ -139,11 +139,19 @@ def main() -> int:
         run_step(r, events)
     torch.cuda.synchronize()
     per = {}
-    for label, fl, e0, e1 in events:
+    extract_ms = 0.0
+    n_extract = 0
+    for label, fl, e0, e1, xe in events:
         d = per.setdefault(label, [0, 0.0, 0.0])
+        ms = e0.elapsed_time(e1)
+        if xe is not None:
+            x = xe[0].elapsed_time(xe[1])
+            extract_ms += x
+            n_extract += 1
+            ms = max(ms - x, 0.0)
         d[0] += 1
         d[1] += fl
-        d[2] += e0.elapsed_time(e1)
+        d[2] += ms
     kernels = {k: {"launches": v[0], "avg_ms": v[2] / v[0], "tflops": v[1] / (v[2] * 1e-3) / 1e12}
                for k, v in per.items()}
     dom = max(per.items(), key=lambda kv: kv[1][2])
@@ -151,7 +159,11 @@ def main() -> int:
     dom_tflops = dom[1][1] / (dom[1][2] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s",
                 "frac": dom_tflops / peak, "traffic": None,
-                "avg_launch_ms": dom[1][2] / dom[1][0], "launches": dom[1][0]}
+                "avg_launch_ms": dom[1][2] / dom[1][0], "launches": dom[1][0],
+                "note": "achieved = kept FLOPs of the launches of this instantiation / their summed durations "
+                        "(HIP events on the launch stream)"}
+    extract = {"kernel": "compact_cols_kernel", "launches": n_extract,
+               "avg_ms": extract_ms / n_extract if n_extract else None}
 
     # ---- time vs ratio (median of a few steps each) --------------------------
     sweep = {}
@@ -205,10 +217,11 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: M={M} tokens, projections "
                                + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
                                + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
-                   "path": "resize_select + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation"},
+                   "path": "resize_select + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
+                           "with the optional scratch buffer for extracted activation columns"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "by_ratio": sweep,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "extract": extract, "by_ratio": sweep,
     }
     print(json.dumps(line))
     return 0

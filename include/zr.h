@@ -105,6 +105,16 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
  * when no call would use a workspace (fp32).  Pure host function. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
+/* The extraction step on its own (Sec. 3.1: the remaining columns of the input
+ * are concatenated in ascending index order): out[r, q] = in[r, keep_idx[q]] for
+ * q < n_keep, and +0 for n_keep <= q < width, width = n_keep rounded up to 64.
+ *  in [rows x n] ld, out [rows x width] ldo >= width; bf16 only (else DTYPE);
+ *  ld, ldo and n even, in and out 4-byte aligned (else SHAPE).  One launch.
+ * The forward / backward calls run exactly this kernel when given a workspace. */
+int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
+                            const int32_t* keep_idx, int32_t n_keep,
+                            void* out, int64_t ldo, int dtype, void* stream);
+
 /* Forward of the resized linear layer (Sec. 3.1, forward paragraph).
  *  DROP_K: Y = X[:,S] W[S,:]            (full shape, nothing to impute)
  *  DROP_N: Y[:,S] = X W[:,S];  Y[:,P] imputed by `policy`
@@ -159,6 +169,11 @@ int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
  * device int32 used as scratch.  Returns ZR_OK or ZR_ERR_INDEX. */
 int zr_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t n,
                          int32_t* flag, void* stream);
+
+/* Debugging / profiling aid: name (as a profiler prints it, without namespaces) of
+ * the GEMM kernel instantiation the last forward / backward call of this
+ * process launched.  Not thread safe. */
+const char* zr_debug_last_kernel(void);
 
 #ifdef __cplusplus
 }

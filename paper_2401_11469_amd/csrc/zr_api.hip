@@ -89,6 +89,22 @@ const char* zr_status_string(int status)
     }
 }
 
+const char* zr_debug_last_kernel(void) { return g_last_kernel; }
+
+int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
+                            const int32_t* keep_idx, int32_t n_keep,
+                            void* out, int64_t ldo, int dtype, void* stream)
+{
+    if (!in || !keep_idx || !out) return ZR_ERR_NULL;
+    if (dtype != ZR_BF16) return ZR_ERR_DTYPE;
+    if (rows < 1 || n < 1 || ld < n) return ZR_ERR_SHAPE;
+    if (n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
+    const int width = round_up64(n_keep);
+    if (ldo < width || ldo % 2 != 0 || ld % 2 != 0 || n % 2 != 0) return ZR_ERR_SHAPE;
+    if ((uintptr_t)in % 4 != 0 || (uintptr_t)out % 4 != 0) return ZR_ERR_SHAPE;
+    return launch_compact_cols(in, ld, rows, n, keep_idx, n_keep, out, ldo, width, (hipStream_t)stream);
+}
+
 int64_t zr_keep_count(int64_t n, double ratio)
 {
     if (n < 0 || !(ratio >= 0.0) || !(ratio < 1.0)) return -1;

@@ -66,6 +66,7 @@ struct GemmDesc {
     int dtype;
 };
 
+extern char g_last_kernel[128];
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
 int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,

@@ -24,6 +24,8 @@
 //   ELEM  element loads through an index list on the contiguous axis (e.g.
 //         X[:,S], W[:,S]) - two bf16 loads are packed into one LDS word - and
 //         the fallback for unaligned tensors.
+#include <cstdio>
+
 #include "zr_common.h"
 
 namespace zr {
@@ -551,6 +553,8 @@ int launch_inst(const KArgs& k, hipStream_t stream)
         if (e != hipSuccess) return ZR_ERR_HIP;
         attr_set = true;
     }
+    snprintf(g_last_kernel, sizeof(g_last_kernel), "gemm_kernel<%d, %s, %s, %s, %s, %d, %d>", DT,
+             ACC ? "true" : "false", AVEC ? "true" : "false", BCC ? "true" : "false", BVEC ? "true" : "false", BM, BN);
     KArgs kk = k;
     kk.tiles_j = (k.J + BN - 1) / BN;
     const int64_t tiles = (int64_t)((k.I + BM - 1) / BM) * kk.tiles_j;

@@ -21,9 +21,13 @@
 //        permute (loader PG).
 // The epilogue composes full-width output rows in LDS order: kept columns get
 // their result, dropped columns of the tile's span get +0, stored as dwords.
+#include <cstdio>
+
 #include "zr_common.h"
 
 namespace zr {
+
+char g_last_kernel[128] = "";   // name of the last GEMM kernel launched (debugging aid)
 
 namespace {
 
@@ -147,6 +151,7 @@ __device__ __forceinline__ void interleave4x8(const uint4 r[4], uint2 w[8])
 // Contraction axis contiguous in memory, 16-byte loads, optional row list.
 template <int R, int NT>
 struct LdPV {
+    static constexpr const char* NAME = "LdPV";
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -192,6 +197,7 @@ struct LdPV {
 // dword with one byte permute.
 template <int R, int NT>
 struct LdPG {
+    static constexpr const char* NAME = "LdPG";
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -252,6 +258,7 @@ struct LdPG {
 // consecutive columns, interleaved in registers; optional row list on c.
 template <int R, int NT>
 struct LdQV {
+    static constexpr const char* NAME = "LdQV";
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -324,6 +331,7 @@ struct LdQV {
 // kept sets) are processed unpipelined in commit().
 template <int R, int NT>
 struct LdQG {
+    static constexpr const char* NAME = "LdQG";
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -439,6 +447,7 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
 // its 8 chunks at positions chunk ^ (i & 7).
 template <int R, int NT>
 struct DmaP {
+    static constexpr const char* NAME = "DmaP";
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
     static constexpr int WORDS = R * 32;
@@ -487,6 +496,7 @@ struct DmaP {
 // 4 (c) x 16 (columns) block read by its 16-lane group.
 template <int R, int NT>
 struct DmaQ {
+    static constexpr const char* NAME = "DmaQ";
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
     static constexpr int WORDS = BK * R / 2;
@@ -780,6 +790,8 @@ int launch_tile(const FArgs& a, hipStream_t stream)
             return ZR_ERR_HIP;
         attr_set = true;
     }
+    snprintf(g_last_kernel, sizeof(g_last_kernel), "fast_kernel<%s, %s, %d, %d, %d, %d>",
+             LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
     FArgs k = a;
     k.tiles_i = (a.I + BM - 1) / BM;
     k.tiles_j = (a.J + BN - 1) / BN;

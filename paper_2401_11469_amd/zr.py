@@ -45,6 +45,10 @@ _lib.zr_resized_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i6
 _lib.zr_resized_linear_bwd.restype = ctypes.c_int
 _lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, ctypes.c_int, _vp]
 _lib.zr_impute.restype = ctypes.c_int
+_lib.zr_extract_kept_columns.argtypes = [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
+_lib.zr_extract_kept_columns.restype = ctypes.c_int
+_lib.zr_debug_last_kernel.argtypes = []
+_lib.zr_debug_last_kernel.restype = ctypes.c_char_p
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -190,6 +194,23 @@ def impute(out: torch.Tensor, axis: int, keep_idx: torch.Tensor, policy: int = Z
     _check(_lib.zr_impute(op, ld, out.shape[0], out.shape[1], axis, keep_idx.data_ptr(),
                           keep_idx.numel(), policy, pp, _dtype_code(out), _stream(stream)))
     return out
+
+
+def extract_kept_columns(inp: torch.Tensor, keep_idx: torch.Tensor, out: Optional[torch.Tensor] = None,
+                         stream=None) -> torch.Tensor:
+    """out[r, q] = inp[r, keep_idx[q]], zero padded to a multiple of 64 columns (bf16)."""
+    rows, n = inp.shape
+    width = (keep_idx.numel() + 63) // 64 * 64
+    if out is None:
+        out = torch.empty((rows, width), dtype=inp.dtype, device=inp.device)
+    (ip, ld), (op, ldo) = _mat(inp, "inp"), _mat(out, "out")
+    _check(_lib.zr_extract_kept_columns(ip, ld, rows, n, keep_idx.data_ptr(), keep_idx.numel(), op, ldo,
+                                        _dtype_code(inp), _stream(stream)))
+    return out
+
+
+def debug_last_kernel() -> str:
+    return _lib.zr_debug_last_kernel().decode()
 
 
 def validate_keep_idx(keep_idx: torch.Tensor, n: int, stream=None) -> bool:

@@ -31,7 +31,8 @@ def _declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_symbols()
     assert {"zr_keep_count", "zr_resize_select", "zr_resized_linear_fwd", "zr_resized_linear_bwd",
-            "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes"} <= set(names)
+            "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes",
+            "zr_extract_kept_columns", "zr_debug_last_kernel"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
