@@ -37,19 +37,22 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint16_t E;
 
-// LDS tile layout, the same for every operand kind: 8 blocks (one per group of
-// 8 contraction indices); inside a block every tile row owns one 16-byte slot
+// LDS tile layout of the register-staged loaders: 8 blocks (one per group of 8
+// contraction indices); inside a block every tile row owns one 16-byte slot
 // holding its 8 bf16 of that group, so an MFMA k-vector is one ds_read_b128.
-// The LDS serves 16-byte accesses 8 lanes at a time over 32 banks (128 bytes):
-// 8 consecutive lanes must hit 8 different slots modulo 8.  Rows are placed at
-// slot(i) = i + (i >> 3), which gives that both for 8 consecutive rows (fragment
-// reads, row-wise writes) and for rows 8 apart (writes of the loaders whose
-// lanes hold 8 consecutive columns each); blocks are 1 slot out of phase so
-// that lanes writing the same row of different blocks do not collide either.
+// The LDS serves a 16-byte access 16 lanes at a time over 64 banks (256 bytes),
+// so 16 lanes must hit 16 different slots modulo 16.  With i = 128 b + 8 a + m
+// (m = i & 7) the row sits at slot 128 b + 16 m + ((a + 2 m) & 15): that holds
+// both for 16 consecutive rows (fragment reads) and for rows 8 apart (writes of
+// the loaders whose lanes hold 8 consecutive columns each).
 template <int R> struct Tile {
-    static constexpr int BW = (R + R / 8 + 1) * 4;    // words per block
+    static constexpr int BW = R * 4 + 4;              // words per block (blocks 1 bank group out of phase)
     static constexpr int WORDS = 8 * BW;
-    static __device__ __forceinline__ int slot(int i) { return i + (i >> 3); }
+    static __device__ __forceinline__ int slot(int i)
+    {
+        const int m = i & 7, a = (i >> 3) & 15;
+        return (i & ~127) + 16 * m + ((a + 2 * m) & 15);
+    }
 };
 
 typedef __attribute__((address_space(3))) void* lds_void;
@@ -67,15 +70,16 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 u)
 // w0: first tile row of this wavefront; t: 32-row sub-tile; step: 16 contraction
 // indices; lanes 0-31 take the first 8 of them, lanes 32-63 the other 8.
 template <int R> struct SlotReader {
-    int off;
+    int off[4];     // word offset of this lane's row in each of the wavefront's 32-row sub-tiles
     __device__ __forceinline__ void setup(int w0, int lane)
     {
-        off = Tile<R>::slot(w0 + (lane & 31)) * 4 + (lane >> 5) * Tile<R>::BW;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            off[t] = Tile<R>::slot(min(w0 + t * 32 + (lane & 31), R - 1)) * 4 + (lane >> 5) * Tile<R>::BW;
     }
     __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
     {
-        // 32 rows further = 36 slots = 144 words
-        return as_frag(*(const uint4*)(stage + off + 2 * step * Tile<R>::BW + t * 144));
+        return as_frag(*(const uint4*)(stage + off[t] + 2 * step * Tile<R>::BW));
     }
 };
 
@@ -95,6 +99,9 @@ struct FArgs {
     int epilogue;
     const int32_t* keep;
     int out_full;
+    // sub-rectangle of D this launch covers, in elements (multiples of 256 except at
+    // the far edges of D) and its tile grid
+    int i_base, j_base, i_end, j_end;
     int tiles_i, tiles_j;
 };
 
@@ -316,9 +323,9 @@ struct LdQV {
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[it][u] = sel4(u < left_[it], v[it][u]);
             interleave4x8(v[it], w);
-            uint32_t* dst = lds + (kq >> 1) * T::BW + (kq & 1) * 2 + jc * 36;  // slot(8 jc + m) = 9 jc + m
+            uint32_t* dst = lds + (kq >> 1) * T::BW + (kq & 1) * 2 + (jc >> 4) * 512;
 #pragma unroll
-            for (int m = 0; m < 8; ++m) *(uint2*)(dst + m * 4) = w[m];
+            for (int m = 0; m < 8; ++m) *(uint2*)(dst + (16 * m + ((jc + 2 * m) & 15)) * 4) = w[m];   // slot(8 jc + m)
         }
     }
 };
@@ -443,8 +450,9 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
     __builtin_amdgcn_global_load_lds((glb_void)gptr, (lds_void)lds_uniform, 16, 0, 0);
 }
 
-// Contraction axis contiguous in memory (optional row list): LDS row i holds
-// its 8 chunks at positions chunk ^ (i & 7).
+// Contraction axis contiguous in memory (optional row list): LDS row i (128
+// bytes) holds its 8 chunks at positions chunk ^ ((i >> 1) & 7), which spreads
+// 16 consecutive rows of one chunk over all 64 banks.
 template <int R, int NT>
 struct DmaP {
     static constexpr const char* NAME = "DmaP";
@@ -461,7 +469,7 @@ struct DmaP {
         __device__ __forceinline__ void setup(int w0, int lane)
         {
             off = (w0 + (lane & 31)) * 32;
-            x = ((lane & 7) << 2) ^ ((lane >> 5) << 2);     // word offset of chunk (grp ^ (row & 7))
+            x = (((lane >> 1) & 7) << 2) ^ ((lane >> 5) << 2);   // word offset of chunk grp ^ ((row >> 1) & 7)
         }
         __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
         {
@@ -472,7 +480,10 @@ struct DmaP {
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int)
     {
         const int lane = tid & 63, wave = tid >> 6;
-        chunk_ = ((lane & 7) ^ (lane >> 3)) * 8;
+        // rows of an instruction: 8 (wave + NW q) + (lane >> 3); NW is even, so
+        // (row >> 1) & 7 = 4 (wave & 1) + (lane >> 4) for every q
+        static_assert(NW % 2 == 0, "the swizzle below assumes an even number of wavefronts");
+        chunk_ = ((lane & 7) ^ (((lane >> 4) & 3) | ((wave & 1) << 2))) * 8;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
             const int i = min(r0 + 8 * (wave + NW * q) + (lane >> 3), rlim - 1);
@@ -651,7 +662,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int within = t - gidx * grp_sz;
     const int ti = first_i + within % rows_in;
     const int tj = within / rows_in;
-    const int i0 = ti * BM, j0 = tj * BN;
+    const int i0 = g.i_base + ti * BM, j0 = g.j_base + tj * BN;
 
     if (LA::NEEDS_IDX) {
         const int cnt = min(BM, g.I - i0);
@@ -780,8 +791,9 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 // Host side
 // ---------------------------------------------------------------------------
 template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
-int launch_tile(const FArgs& a, hipStream_t stream)
+int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream)
 {
+    if (i_end <= i_base || j_end <= j_base) return ZR_OK;
     constexpr int smem = fast_smem_bytes<LA<BM, 64 * WM * WN>::WORDS, LB<BN, 64 * WM * WN>::WORDS, BM, BN>();
     auto fn = fast_kernel<LA, LB, BM, BN, WM, WN>;
     static bool attr_set = false;
@@ -793,8 +805,9 @@ int launch_tile(const FArgs& a, hipStream_t stream)
     snprintf(g_last_kernel, sizeof(g_last_kernel), "fast_kernel<%s, %s, %d, %d, %d, %d>",
              LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
     FArgs k = a;
-    k.tiles_i = (a.I + BM - 1) / BM;
-    k.tiles_j = (a.J + BN - 1) / BN;
+    k.i_base = i_base; k.i_end = i_end; k.j_base = j_base; k.j_end = j_end;
+    k.tiles_i = (i_end - i_base + BM - 1) / BM;
+    k.tiles_j = (j_end - j_base + BN - 1) / BN;
     const int64_t tiles = (int64_t)k.tiles_i * k.tiles_j;
     const int64_t grid = (tiles + 7) / 8 * 8;
     if (grid > 0x7fffffff) return ZR_ERR_LIMIT;
@@ -802,13 +815,65 @@ int launch_tile(const FArgs& a, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// Tile schedule.  The chip has 256 CUs; a 256 x 256 tile occupies one CU (one
+// "round" = 256 such tiles), two 128 x 128 tiles share a CU.  A grid whose tile
+// count is just above a multiple of 256 would leave most CUs idle in its last
+// round, so D is cut into a panel of big tiles that fills whole rounds and a
+// remainder panel of small tiles (a second launch), whichever cut of rows or
+// columns is estimated cheapest.  Costs are in units of one big-tile round;
+// the constants come from measurements on the workload shapes.
+struct Sched {
+    int big_i_end, big_j_end;   // big tiles cover [0, big_i_end) x [0, big_j_end); 0 = no big panel
+    bool cut_rows;              // the remainder panel is rows [big_i_end, I) (else columns [big_j_end, J))
+};
+
+inline double small_cost(int64_t ts)
+{
+    if (ts <= 0) return 0.0;
+    if (ts <= 256) return 0.42;                       // one small tile per CU
+    return 0.70 * (double)((ts + 511) / 512);         // two per CU
+}
+
+inline Sched plan_tiles(int I, int J)
+{
+    const int ti = (I + 255) / 256, tj = (J + 255) / 256;
+    const int64_t T = (int64_t)ti * tj;
+    auto smalls = [](int rows, int cols) { return (int64_t)((rows + 127) / 128) * ((cols + 127) / 128); };
+    Sched best{I, J, true};
+    double best_cost = (double)((T + 255) / 256);                  // all big
+    {
+        const double c = small_cost(smalls(I, J));                 // all small
+        if (c < best_cost) { best_cost = c; best = Sched{0, 0, true}; }
+    }
+    for (int q = 1; q * 256 < T; ++q) {                            // q full rounds of big tiles
+        const int rb = (int)((int64_t)q * 256 / tj);               // big tile-rows
+        if (rb >= 1 && rb < ti) {
+            const double c = (double)(((int64_t)rb * tj + 255) / 256) + small_cost(smalls(I - rb * 256, J));
+            if (c < best_cost) { best_cost = c; best = Sched{rb * 256, J, true}; }
+        }
+        const int cb = (int)((int64_t)q * 256 / ti);               // big tile-columns
+        if (cb >= 1 && cb < tj) {
+            const double c = (double)(((int64_t)cb * ti + 255) / 256) + small_cost(smalls(I, J - cb * 256));
+            if (c < best_cost) { best_cost = c; best = Sched{I, cb * 256, false}; }
+        }
+    }
+    return best;
+}
+
 template <template <int, int> class LA, template <int, int> class LB>
 int launch_shape(const FArgs& a, hipStream_t stream)
 {
-    // tile choice: the largest tile whose grid still fills the 256 CUs reasonably
-    const int64_t t256 = (int64_t)((a.I + 255) / 256) * ((a.J + 255) / 256);
-    if (t256 >= 200) return launch_tile<LA, LB, 256, 256, 2, 4>(a, stream);
-    return launch_tile<LA, LB, 128, 128, 2, 2>(a, stream);
+    const Sched sc = plan_tiles(a.I, a.J);
+    if (sc.big_i_end == 0)                     // everything on small tiles
+        return launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, 0, a.J, stream);
+    int st = launch_tile<LA, LB, 256, 256, 2, 4>(a, 0, sc.big_i_end, 0, sc.big_j_end, stream);
+    if (st != ZR_OK || (sc.big_i_end >= a.I && sc.big_j_end >= a.J)) return st;
+    char big[128];
+    snprintf(big, sizeof(big), "%s", g_last_kernel);
+    if (sc.cut_rows) st = launch_tile<LA, LB, 128, 128, 2, 2>(a, sc.big_i_end, a.I, 0, a.J, stream);
+    else st = launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, sc.big_j_end, a.J, stream);
+    snprintf(g_last_kernel, sizeof(g_last_kernel), "%.60s + 128x128 remainder panel", big);
+    return st;
 }
 
 }  // namespace
@@ -838,6 +903,7 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     a.I = d.I; a.J = d.J; a.C = d.C;
     a.out = (E*)d.out; a.ldo = d.ldo; a.epilogue = d.epilogue; a.keep = d.keep_idx; a.out_full = d.out_full;
     a.tiles_i = a.tiles_j = 0;
+    a.i_base = a.j_base = a.i_end = a.j_end = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;
     // Direct-to-LDS loaders cannot zero the contraction tail of the last tile
     // themselves: either the tiles are full, or one operand supplies the zeros
