@@ -32,6 +32,10 @@ char g_last_kernel[128] = "";   // name of the last GEMM kernel launched (debugg
 namespace {
 
 constexpr int BK = 64;           // contraction depth of one LDS tile (bf16 elements)
+#ifndef ZR_BIG_WM
+#define ZR_BIG_WM 2
+#define ZR_BIG_WN 4
+#endif
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -596,18 +600,46 @@ __device__ __forceinline__ void pipeline_step(
         if constexpr (LA::DMA) la.issue(g.A, wr, c_next, g.C, tid); else la.fetch(g.A, c_next, g.C, tid);
         if constexpr (LB::DMA) lb.issue(g.B, wr + A_WORDS, c_next, g.C, tid); else lb.fetch(g.B, c_next, g.C, tid);
     }
+    if constexpr (LA::DMA && LB::DMA) {
+        // No staging registers are live here, so there is room to request the
+        // fragments of step s+1 before the MFMAs of step s are issued: the LDS
+        // latency hides behind this wavefront's own MFMAs.
+        bf16x8 af[2][TM], bf[2][TN];
 #pragma unroll
-    for (int step = 0; step < BK / 16; ++step) {
-        bf16x8 af[TM], bf[TN];
+        for (int a = 0; a < TM; ++a) af[0][a] = ra.read(rd, a, 0);
 #pragma unroll
-        for (int a = 0; a < TM; ++a) af[a] = ra.read(rd, a, step);
+        for (int b = 0; b < TN; ++b) bf[0][b] = rb.read(rd + A_WORDS, b, 0);
 #pragma unroll
-        for (int b = 0; b < TN; ++b) bf[b] = rb.read(rd + A_WORDS, b, step);
+        for (int step = 0; step < BK / 16; ++step) {
+            const int cb = step & 1, nb = cb ^ 1;
+            if (step + 1 < BK / 16) {
 #pragma unroll
-        for (int a = 0; a < TM; ++a)
+                for (int a = 0; a < TM; ++a) af[nb][a] = ra.read(rd, a, step + 1);
 #pragma unroll
-            for (int b = 0; b < TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < TN; ++b) bf[nb][b] = rb.read(rd + A_WORDS, b, step + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);       // keep the prefetch above the MFMAs
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][a], bf[cb][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll
+        for (int step = 0; step < BK / 16; ++step) {
+            bf16x8 af[TM], bf[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) af[a] = ra.read(rd, a, step);
+#pragma unroll
+            for (int b = 0; b < TN; ++b) bf[b] = rb.read(rd + A_WORDS, b, step);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
     }
     if (more) {
         if constexpr (!LA::DMA) la.commit(g.A, wr, tid);
@@ -866,7 +898,7 @@ int launch_shape(const FArgs& a, hipStream_t stream)
     const Sched sc = plan_tiles(a.I, a.J);
     if (sc.big_i_end == 0)                     // everything on small tiles
         return launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, 0, a.J, stream);
-    int st = launch_tile<LA, LB, 256, 256, 2, 4>(a, 0, sc.big_i_end, 0, sc.big_j_end, stream);
+    int st = launch_tile<LA, LB, 256, 256, ZR_BIG_WM, ZR_BIG_WN>(a, 0, sc.big_i_end, 0, sc.big_j_end, stream);
     if (st != ZR_OK || (sc.big_i_end >= a.I && sc.big_j_end >= a.J)) return st;
     char big[128];
     snprintf(big, sizeof(big), "%s", g_last_kernel);
