@@ -117,6 +117,23 @@ __device__ __forceinline__ E to_bf16(float f)
     return x.u;
 }
 
+// rows[q] <- list[idx[q]] clamped into [0, n) (or idx[q] itself without a list); the
+// loads are issued together under ONE uniform branch instead of one branch + wait each
+template <int N>
+__device__ __forceinline__ void lookup_rows(const int32_t* list, int n, const int (&idx)[N], int (&rows)[N])
+{
+    if (list) {
+        int v[N];
+#pragma unroll
+        for (int q = 0; q < N; ++q) v[q] = list[idx[q]];
+#pragma unroll
+        for (int q = 0; q < N; ++q) rows[q] = clamp_idx(v[q], n);
+    } else {
+#pragma unroll
+        for (int q = 0; q < N; ++q) rows[q] = idx[q];
+    }
+}
+
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
 __device__ __forceinline__ uint4 sel4(bool ok, uint4 v)
 {
@@ -175,13 +192,13 @@ struct LdPV {
 
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int)
     {
+        int idx[N], rows[N];
 #pragma unroll
-        for (int it = 0; it < N; ++it) {
-            const int q = tid + NT * it;
-            const int i = min(r0 + (q >> 3), rlim - 1);
-            const int srow = op.map_s ? clamp_idx(op.map_s[i], op.n_s) : i;
-            ptr[it] = op.base + (size_t)srow * (size_t)op.ld + (q & 7) * 8;
-        }
+        for (int it = 0; it < N; ++it) idx[it] = min(r0 + ((tid + NT * it) >> 3), rlim - 1);
+        lookup_rows<N>(op.map_s, op.n_s, idx, rows);
+#pragma unroll
+        for (int it = 0; it < N; ++it)
+            ptr[it] = op.base + (size_t)rows[it] * (size_t)op.ld + ((tid + NT * it) & 7) * 8;
     }
     __device__ __forceinline__ void fetch(const FOp& op, int c0, int C, int tid)
     {
@@ -285,15 +302,16 @@ struct LdQV {
 
     __device__ __forceinline__ void rows_for(const FOp& op, int c0, int C, int tid)
     {
+        int idx[N * 4], rows[N * 4];
 #pragma unroll
-        for (int it = 0; it < N; ++it) {
-            const int c = c0 + 4 * ((tid + NT * it) / UPR);
+        for (int it = 0; it < N; ++it)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int cu = min(c + u, C - 1);
-                rr[it][u] = op.map_s ? clamp_idx(op.map_s[cu], op.n_s) : cu;
-            }
-        }
+            for (int u = 0; u < 4; ++u) idx[it * 4 + u] = min(c0 + 4 * ((tid + NT * it) / UPR) + u, C - 1);
+        lookup_rows<N * 4>(op.map_s, op.n_s, idx, rows);
+#pragma unroll
+        for (int it = 0; it < N; ++it)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) rr[it][u] = rows[it * 4 + u];
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
@@ -488,12 +506,12 @@ struct DmaP {
         // (row >> 1) & 7 = 4 (wave & 1) + (lane >> 4) for every q
         static_assert(NW % 2 == 0, "the swizzle below assumes an even number of wavefronts");
         chunk_ = ((lane & 7) ^ (((lane >> 4) & 3) | ((wave & 1) << 2))) * 8;
+        int idx[N], rows[N];
 #pragma unroll
-        for (int q = 0; q < N; ++q) {
-            const int i = min(r0 + 8 * (wave + NW * q) + (lane >> 3), rlim - 1);
-            const int srow = op.map_s ? clamp_idx(op.map_s[i], op.n_s) : i;
-            ptr[q] = op.base + (size_t)srow * (size_t)op.ld;
-        }
+        for (int q = 0; q < N; ++q) idx[q] = min(r0 + 8 * (wave + NW * q) + (lane >> 3), rlim - 1);
+        lookup_rows<N>(op.map_s, op.n_s, idx, rows);
+#pragma unroll
+        for (int q = 0; q < N; ++q) ptr[q] = op.base + (size_t)rows[q] * (size_t)op.ld;
     }
     __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
     {
@@ -552,11 +570,10 @@ struct DmaQ {
     }
     __device__ __forceinline__ void rows_for(const FOp& op, int c0, int C, int tid)
     {
+        int idx[N];
 #pragma unroll
-        for (int q = 0; q < N; ++q) {
-            const int c = min(c0 + tile_row(q, tid), C - 1);
-            rr[q] = op.map_s ? clamp_idx(op.map_s[c], op.n_s) : c;
-        }
+        for (int q = 0; q < N; ++q) idx[q] = min(c0 + tile_row(q, tid), C - 1);
+        lookup_rows<N>(op.map_s, op.n_s, idx, rr);
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {

@@ -17,7 +17,7 @@ DROP_N, DROP_K = 0, 1
 ZERO, AVERAGE, SAME = 0, 1, 2
 F32, BF16 = 0, 1
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzr.so")
+_LIB_PATH = os.environ.get("ZR_LIBZR_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzr.so")
 if not os.path.exists(_LIB_PATH):
     raise ImportError(
         f"{_LIB_PATH} is missing: build it first (python -m paper_2401_11469_amd.build); "
