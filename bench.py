@@ -187,6 +187,47 @@ def main() -> int:
                                  "speedup_vs_first": base_ms / med,
                                  "kept_fraction": fl / step_flops(cfg.ratios[0])}
 
+    # ---- HBM-bound helpers: selector and stand-alone imputation ----------------
+    def timed(fn, n=20):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    aux = {}
+    p0 = projs[0]
+    aux["select_single_us"] = {
+        f"n={p['n']}": timed(lambda p=p: zr.resize_select(p["scores"], 0.25, keep_idx=p["keep"], drop_idx=p["drop"])) * 1e3
+        for p in projs}
+    nb, nn = 4096, 4096
+    sc = torch.rand((nb, nn), dtype=torch.float32, device=dev)
+    kb = torch.empty((nb, nn), dtype=torch.int32, device=dev)
+    db = torch.empty((nb, nn), dtype=torch.int32, device=dev)
+    ms = timed(lambda: zr.resize_select(sc, 0.25, keep_idx=kb, drop_idx=db), n=5)
+    aux["select_batched"] = {"batch": nb, "n": nn, "ms": ms, "GB/s": 8.0 * nb * nn / (ms * 1e-3) / 1e9,
+                             "frac_hbm_peak": 8.0 * nb * nn / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "bytes": "algorithmic: 4n read + 4n written per vector"}
+    del sc, kb, db
+    keep25, _ = zr.resize_select(p0["scores"], 0.25)
+    ncols = p0["Y"].shape[1] if p0["pr"].mode == zr.DROP_N else p0["dX"].shape[1]
+    buf = p0["Y"] if p0["pr"].mode == zr.DROP_N else p0["dX"]
+    prev = torch.zeros_like(buf)
+    esz = buf.element_size()
+    dropped_bytes = esz * M * (ncols - keep25.numel())
+    kept_bytes = esz * M * keep25.numel()
+    for name, pol, nbytes in (("zero", zr.ZERO, dropped_bytes), ("same", zr.SAME, 2 * dropped_bytes),
+                              ("average", zr.AVERAGE, kept_bytes + dropped_bytes)):
+        ms = timed(lambda pol=pol: zr.impute(buf, 1, keep25, pol, prev if pol == zr.SAME else None))
+        aux[f"impute_{name}"] = {"shape": [M, ncols], "ratio": 0.25, "ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9,
+                                 "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del prev
+
     # ---- CPU oracle on the host cores, bounded sample -------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -221,7 +262,7 @@ def main() -> int:
                            "with the optional scratch buffer for extracted activation columns"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "extract": extract, "by_ratio": sweep,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "extract": extract, "by_ratio": sweep, "aux": aux,
     }
     print(json.dumps(line))
     return 0

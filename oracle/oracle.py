@@ -185,6 +185,17 @@ def _recover(pruned: np.ndarray, full_shape, axis: int, keep_idx: np.ndarray) ->
     return full
 
 
+def extract_kept_columns(A, keep_idx, width: Optional[int] = None) -> np.ndarray:
+    """The pruning step on its own (Sec. 3.1): the kept columns of A concatenated
+    in ascending index order; optionally zero-padded on the right to ``width``."""
+    A = np.asarray(A, dtype=np.float64)
+    S = np.asarray(keep_idx, dtype=np.int64)
+    out = A[:, S]
+    if width is not None and width > out.shape[1]:
+        out = np.concatenate([out, np.zeros((A.shape[0], width - out.shape[1]))], axis=1)
+    return out
+
+
 # --------------------------------------------------------------------------
 # Resized linear layer
 # --------------------------------------------------------------------------

@@ -100,6 +100,14 @@ def test_argument_validation_returns_before_any_gpu_work(lib):
     assert imp(p, 8, 4, 8, 2, p, 4, 0, None, 1, None) == 2
     assert imp(p, 8, 4, 8, 1, p, 9, 0, None, 1, None) == 4
     assert imp(p, 8, 4, 8, 1, p, 4, 2, None, 1, None) == 7
+    ext = lib.zr_extract_kept_columns
+    ext.argtypes = [vp, i64, i32, i32, vp, i32, vp, i64, ctypes.c_int, vp]
+    ext.restype = ctypes.c_int
+    assert ext(None, 8, 4, 8, p, 4, p, 64, 1, None) == 1
+    assert ext(p, 8, 4, 8, p, 4, p, 64, 0, None) == 5          # bf16 only
+    assert ext(p, 8, 4, 8, p, 9, p, 64, 1, None) == 4
+    assert ext(p, 8, 4, 8, p, 4, p, 32, 1, None) == 2          # ldo < 64
+    assert ext(p, 7, 4, 7, p, 4, p, 64, 1, None) == 2          # odd row length
     bwd = lib.zr_resized_linear_bwd
     bwd.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
                     ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]

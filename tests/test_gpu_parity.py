@@ -163,6 +163,23 @@ def test_impute_parity(zr, torch_mod, oracle, dtype, axis, policy, rows, cols):
         assert torch.all(base[:, cols:] == 777.0)
 
 
+@pytest.mark.parametrize("rows,n", [(1, 2), (9, 64), (37, 130), (130, 1000), (64, 4096)])
+def test_extract_kept_columns_bit_exact(zr, torch_mod, oracle, rows, n):
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(rows + n))
+    A = wl.round_to_bf16(g.standard_normal((rows, n)).astype(np.float32))
+    Ag = to_gpu(torch, A, "bf16")
+    for n_keep in sorted({1, 2, max(1, n // 2), max(1, n - 1), n}):
+        S = subset(n_keep + 3, n, n_keep)
+        width = (n_keep + 63) // 64 * 64
+        out = torch.full((rows, width + 8), 777.0, dtype=torch.bfloat16, device="cuda")
+        zr.extract_kept_columns(Ag, idx_gpu(torch, S), out=out[:, :width])
+        want = oracle.extract_kept_columns(A, S, width)
+        assert np.array_equal(to_np(out[:, :width]), want)
+        assert not np.any(np.signbit(to_np(out[:, n_keep:width])))
+        assert torch.all(out[:, width:] == 777.0)
+
+
 # ------------------------------------------------------------------- GEMMs ---
 
 def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False):

@@ -380,6 +380,13 @@ def test_layer_with_other_policies_differs_only_at_dropped_positions(oracle, pol
                 assert np.allclose(dWp[:, P], dWz[:, S].mean(axis=1, keepdims=True), rtol=0, atol=1e-13)
 
 
+def test_extract_kept_columns_is_plain_indexing(oracle):
+    A = np.arange(24, dtype=np.float64).reshape(3, 8)
+    got = oracle.extract_kept_columns(A, np.array([1, 4, 6], dtype=np.int32), width=5)
+    want = np.array([[1, 4, 6, 0, 0], [9, 12, 14, 0, 0], [17, 20, 22, 0, 0]], dtype=np.float64)   # by hand
+    assert np.array_equal(got, want)
+
+
 # --------------------------------------------------------------- workloads ---
 
 def test_workload_shapes_and_flops():
