@@ -8,7 +8,9 @@
 // those equal to T, writing kept and pruned indices by prefix position, which
 // makes both lists ascending by construction.
 //
-// One workgroup of 1024 threads (16 wavefronts of 64) per score vector.
+// One workgroup of 1024 threads (16 wavefronts of 64) per score vector.  Vectors
+// of up to 12288 scores are turned into order keys once and kept in LDS, so
+// the five passes read HBM a single time; longer ones re-read from memory.
 #include "zr_common.h"
 
 namespace zr {
@@ -28,10 +30,14 @@ __device__ __forceinline__ uint32_t order_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+constexpr int SEL_LDS_KEYS = 12288;    // 48 KB of order keys
+
+template <bool STAGED>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float* __restrict__ scores, int n, int n_keep,
     int32_t* __restrict__ keep_idx, int32_t* __restrict__ drop_idx, int64_t ld_idx)
 {
+    __shared__ uint32_t keys[STAGED ? SEL_LDS_KEYS : 1];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_digit, s_remaining;
     __shared__ uint32_t wave_gt[SEL_WAVES], wave_eq[SEL_WAVES];
@@ -43,6 +49,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     int32_t* keep = keep_idx + (size_t)blockIdx.x * (size_t)ld_idx;
     int32_t* drop = drop_idx ? drop_idx + (size_t)blockIdx.x * (size_t)ld_idx : nullptr;
 
+    if (STAGED) {
+        for (int i = tid; i < n; i += SEL_THREADS) keys[i] = order_key(s[i]);
+        __syncthreads();
+    }
+    auto key_at = [&](int i) -> uint32_t { return STAGED ? keys[i] : order_key(s[i]); };
+
     // ---- radix select of the n_keep-th largest key -------------------------
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)n_keep;
     for (int pass = 0; pass < 4; ++pass) {
@@ -50,7 +62,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
         for (int i = tid; i < n; i += SEL_THREADS) {
-            const uint32_t k = order_key(s[i]);
+            const uint32_t k = key_at(i);
             if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
         }
         __syncthreads();
@@ -92,7 +104,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         const int i = base + tid;
         bool gt = false, eq = false;
         if (i < n) {
-            const uint32_t k = order_key(s[i]);
+            const uint32_t k = key_at(i);
             gt = k > T;
             eq = k == T;
         }
@@ -149,8 +161,12 @@ __global__ void validate_kernel(const int32_t* __restrict__ keep_idx, int n_keep
 int launch_select(const float* scores, int n, int batch, int n_keep,
                   int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream)
 {
-    hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(SEL_THREADS), 0, stream,
-                       scores, n, n_keep, keep_idx, drop_idx, ld_idx);
+    if (n <= SEL_LDS_KEYS)
+        hipLaunchKernelGGL(select_kernel<true>, dim3(batch), dim3(SEL_THREADS), 0, stream,
+                           scores, n, n_keep, keep_idx, drop_idx, ld_idx);
+    else
+        hipLaunchKernelGGL(select_kernel<false>, dim3(batch), dim3(SEL_THREADS), 0, stream,
+                           scores, n, n_keep, keep_idx, drop_idx, ld_idx);
     return hip_status(hipGetLastError());
 }
 
