@@ -130,6 +130,61 @@ def resize_select(scores: np.ndarray, ratio: float) -> Tuple[np.ndarray, np.ndar
 
 
 # --------------------------------------------------------------------------
+# Priority bookkeeping and ratios (Sec. 3.1 Eq. 1; Sec. 3.2; Algorithm 1, the
+# per-layer block before the top-L_pri select)
+# --------------------------------------------------------------------------
+
+def priority_scores(W_t, W_prev, mode: int, prev_scores=None, prev_keep_idx=None) -> np.ndarray:
+    """Weight-variation score of every index of the pruned axis:
+    delta_i = (1/R) * sum_j |w_ji^t - w_ji^(t-1)|, the mean absolute change of
+    slice i over its R elements (columns of W for DROP_N, rows for DROP_K).
+
+    Incremental update: an index that was pruned in the previous epoch (it is
+    not in ``prev_keep_idx``) keeps its previous score instead, because its
+    zero-imputed gradient made its change artificially small.
+    Reading: the algorithm's "sorted" variation list is addressed by original
+    index; sorting is part of the later top-L_pri select."""
+    Wt = np.asarray(W_t, dtype=np.float64)
+    Wp = np.asarray(W_prev, dtype=np.float64)
+    assert Wt.shape == Wp.shape
+    diff = np.abs(Wt - Wp)
+    if mode == DROP_N:
+        delta = diff.sum(axis=0) / float(Wt.shape[0])
+    elif mode == DROP_K:
+        delta = diff.sum(axis=1) / float(Wt.shape[1])
+    else:
+        raise ValueError("mode")
+    if prev_keep_idx is not None:
+        assert prev_scores is not None
+        was_kept = np.zeros(delta.shape[0], dtype=bool)
+        was_kept[np.asarray(prev_keep_idx, dtype=np.int64)] = True
+        delta = np.where(was_kept, delta, np.asarray(prev_scores, dtype=np.float64))
+    return delta
+
+
+def pruning_ratio(T_i: float, T_avg: float, M_i: float, gamma_max: float = 0.9) -> float:
+    """Eq. 1: gamma = (T_i - T_avg) / M_i, the share of the matrix-multiplication
+    time M_i a straggler must shed to close its gap to the average iteration
+    time.  Reading: a task that is not slower than the average prunes nothing
+    (0), and the ratio is capped at ``gamma_max`` (the paper evaluates up to 9/10)."""
+    if not (M_i > 0.0):
+        raise ValueError("M_i must be positive")
+    g = (T_i - T_avg) / M_i
+    return float(min(max(g, 0.0), gamma_max))
+
+
+def layer_ratio(scores, theta: float, alpha: float, gamma: float) -> float:
+    """Differentiated per-layer ratio (Algorithm 1): L_uni = number of indices
+    whose variation exceeds theta (= N_iter * theta_iter); gamma_k = 1 - L_uni / L;
+    the ratio actually used is max(gamma_k, alpha * gamma).
+    Reading: the algorithm's "sum of (delta > theta)" is a count."""
+    s = np.asarray(scores, dtype=np.float64)
+    L = s.shape[0]
+    L_uni = int(np.count_nonzero(s > theta))
+    return float(max(1.0 - L_uni / float(L), alpha * gamma))
+
+
+# --------------------------------------------------------------------------
 # Recovery + imputation (Sec. 3.1, "Consistency Constraint" and the policies)
 # --------------------------------------------------------------------------
 

@@ -387,6 +387,55 @@ def test_extract_kept_columns_is_plain_indexing(oracle):
     assert np.array_equal(got, want)
 
 
+# ------------------------------------------------ priority scores, ratios ---
+
+def test_priority_scores_hand_example(oracle):
+    W_prev = np.array([[1., 2., 3.], [4., 5., 6.]])
+    W_t = np.array([[1.5, 2., 1.], [3., 5., 10.]])
+    # |diff| = [[.5, 0, 2], [1, 0, 4]]
+    assert np.array_equal(oracle.priority_scores(W_t, W_prev, DROP_N), np.array([0.75, 0.0, 3.0]))      # column means
+    assert np.allclose(oracle.priority_scores(W_t, W_prev, DROP_K), np.array([2.5 / 3, 5.0 / 3]), rtol=0, atol=1e-15)
+    # incremental rule: index 1 was pruned last epoch -> keeps its old score
+    got = oracle.priority_scores(W_t, W_prev, DROP_N, prev_scores=np.array([9., 7., 8.]),
+                                 prev_keep_idx=np.array([0, 2], dtype=np.int32))
+    assert np.array_equal(got, np.array([0.75, 7.0, 3.0]))
+
+
+def test_priority_scores_closed_forms(oracle):
+    g = np.random.Generator(np.random.PCG64(41))
+    W_prev = g.standard_normal((13, 9))
+    step = np.abs(g.standard_normal(9))                      # every element of column i moves by +-step_i
+    signs = np.where(g.random((13, 9)) < 0.5, -1.0, 1.0)
+    W_t = W_prev + signs * step[None, :]
+    assert np.allclose(oracle.priority_scores(W_t, W_prev, DROP_N), step, rtol=0, atol=1e-13)
+    assert np.allclose(oracle.priority_scores(W_t, W_prev, DROP_K), np.full(13, step.mean()), rtol=0, atol=1e-13)
+    assert np.array_equal(oracle.priority_scores(W_prev, W_prev, DROP_N), np.zeros(9))
+    # symmetric in its two snapshots, and non-negative
+    a = oracle.priority_scores(W_t, W_prev, DROP_K)
+    assert np.array_equal(a, oracle.priority_scores(W_prev, W_t, DROP_K)) and np.all(a >= 0)
+
+
+def test_pruning_ratio_eq1(oracle):
+    assert oracle.pruning_ratio(12.0, 10.0, 8.0) == 0.25            # (12 - 10) / 8
+    assert oracle.pruning_ratio(9.0, 10.0, 8.0) == 0.0              # faster than average: no pruning
+    assert oracle.pruning_ratio(30.0, 10.0, 8.0) == 0.9             # capped
+    assert oracle.pruning_ratio(30.0, 10.0, 8.0, gamma_max=0.5) == 0.5
+    with pytest.raises(ValueError):
+        oracle.pruning_ratio(1.0, 1.0, 0.0)
+    # shedding gamma * M_i closes the gap exactly
+    T_i, T_avg, M_i = 17.0, 11.0, 16.0
+    assert T_i - oracle.pruning_ratio(T_i, T_avg, M_i) * M_i == T_avg
+
+
+def test_layer_ratio_algorithm1(oracle):
+    scores = np.array([0.5, 0.05, 0.2, 0.01, 0.3, 0.02, 0.0, 0.9])       # 4 of 8 exceed theta = 0.1
+    assert oracle.layer_ratio(scores, 0.1, 0.8, 0.25) == 0.5             # max(1 - 4/8, 0.2)
+    assert oracle.layer_ratio(scores, 0.1, 0.8, 0.9) == 0.8 * 0.9        # the floor alpha * gamma wins
+    assert oracle.layer_ratio(scores, 10.0, 0.8, 0.0) == 1.0             # nothing varies: everything is a candidate
+    assert oracle.layer_ratio(scores, -1.0, 0.8, 0.0) == 0.0
+    assert oracle.layer_ratio(np.array([0.1, 0.1]), 0.1, 0.8, 0.0) == 1.0  # strict comparison
+
+
 # --------------------------------------------------------------- workloads ---
 
 def test_workload_shapes_and_flops():
