@@ -25,6 +25,20 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch (fetched + written) of a GEMM instantiation on the default
+# workload, from the hardware counters FETCH_SIZE / WRITE_SIZE of two
+# `rocprofv3 --pmc` runs of this file, each scaled by what the same counter
+# reads for --calibrate-copy; the summary under profiles/ gives the commands.
+# Counters cannot be read from inside the timed run, so the figures live here.
+PMC_TRAFFIC_BYTES = {
+    "fast_kernel<DmaQ, DmaQ, 256, 256, 2, 4>": 349132586,
+    "fast_kernel<DmaQ, DmaQ, 128, 128, 2, 2>": 288678397,
+    "fast_kernel<DmaP, LdQG, 256, 256, 2, 4>": 306249536,
+    "fast_kernel<DmaP, LdPG, 256, 256, 2, 4>": 324240213,
+    "fast_kernel<DmaP, DmaQ, 256, 256, 2, 4>": 219878583,
+    "fast_kernel<DmaP, DmaP, 256, 256, 2, 4>": 279298933,
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -34,6 +48,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload id (4 = Llama-2-7B TP=4 layer shard)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain copy of known size (the reference dispatch that scales the HBM "
+                         "byte counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one tensor-parallel task's shard on ONE GPU; --gpus must be 1 "
@@ -52,6 +69,20 @@ def main() -> int:
     cfg = wl.CONFIGS[args.config]
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     M = cfg.M
+
+    if args.calibrate_copy:
+        # compact_cols_kernel with the identity index list: reads and writes rows*n*2 bytes
+        rows, n = 65536, 8192
+        src = torch.ones((rows, n), dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        ident = torch.arange(n, dtype=torch.int32, device=dev)
+        for _ in range(10):
+            zr.extract_kept_columns(src, ident, out=dst)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        print(json.dumps({"calibrate_copy": "compact_cols_kernel", "dispatches": 10,
+                          "bytes_read_per_dispatch": rows * n * 2, "bytes_written_per_dispatch": rows * n * 2}))
+        return 0
 
     # ---- inputs resident in HBM before any timing ---------------------------
     projs = []
@@ -158,7 +189,8 @@ def main() -> int:
     peak = PEAK_TFLOPS[cfg.dtype]
     dom_tflops = dom[1][1] / (dom[1][2] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s",
-                "frac": dom_tflops / peak, "traffic": None,
+                "frac": dom_tflops / peak,
+                "traffic": PMC_TRAFFIC_BYTES.get(dom[0]) if args.config == 4 else None,
                 "avg_launch_ms": dom[1][2] / dom[1][0], "launches": dom[1][0],
                 "note": "achieved = kept FLOPs of the launches of this instantiation / their summed durations "
                         "(HIP events on the launch stream)"}
@@ -227,6 +259,23 @@ def main() -> int:
         aux[f"impute_{name}"] = {"shape": [M, ncols], "ratio": 0.25, "ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9,
                                  "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del prev
+    # weight-variation scores of every projection (2 snapshots read once each)
+    pri = {}
+    for p in projs:
+        W = p["W"]
+        Wprev = W.clone()
+        wsb = torch.empty(max(16, zr.priority_workspace_bytes(W.shape[0], W.shape[1], p["pr"].mode)),
+                          dtype=torch.uint8, device=dev)
+        out = torch.empty(p["n"], dtype=torch.float32, device=dev)
+        ms = timed(lambda: zr.priority_scores(W, Wprev, p["pr"].mode, scores=out, workspace=wsb))
+        nbytes = 2.0 * W.numel() * W.element_size()
+        pri[p["pr"].name] = {"shape": list(W.shape), "mode": "DROP_N" if p["pr"].mode == zr.DROP_N else "DROP_K",
+                             "us": ms * 1e3, "GB/s": nbytes / (ms * 1e-3) / 1e9,
+                             "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del Wprev, wsb
+    aux["priority_scores"] = pri
+    cnt = torch.empty(1, dtype=torch.int32, device=dev)
+    aux["count_above_us"] = timed(lambda: zr.count_above(p0["scores"], 0.5, count=cnt)) * 1e3
 
     # ---- CPU oracle on the host cores, bounded sample -------------------------
     cpu = None

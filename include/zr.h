@@ -164,6 +164,38 @@ int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
               const int32_t* keep_idx, int32_t n_keep, int policy, const void* prev,
               int dtype, void* stream);
 
+/* Weight-variation scores (Sec. 3.2 "Priority Pruning"; Algorithm 1):
+ *   scores[i] = mean over the slice's elements of |W_t - W_prev|, for every index
+ *   i of the pruned axis of W[K x N] (columns for ZR_DROP_N, rows for ZR_DROP_K);
+ * incremental update (Sec. 3.2): when prev_keep_idx is given, an index that is
+ * NOT in it (it was pruned in the previous epoch) receives prev_scores[i] instead.
+ *  W_t, W_prev [K x N] with a common leading dimension ld; scores fp32 [n] out;
+ *  prev_keep_idx NULL = plain update (prev_scores ignored).  fp32 sums in a fixed
+ *  order, bitwise repeatable for a given workspace size.
+ *  workspace: optional device scratch of zr_priority_workspace_bytes(K, N, mode)
+ *  bytes (0 for ZR_DROP_K): with it the column sums of ZR_DROP_N are split over
+ *  row ranges so that the launch fills the chip (two launches); NULL or too
+ *  small = one launch that owns whole columns.  The library never allocates.
+ *  Errors: NULL, DTYPE, MODE, SHAPE, INDEX, HIP. */
+int zr_priority_scores(const void* W_t, const void* W_prev, int64_t ld, int32_t K, int32_t N, int mode,
+                       const float* prev_scores, const int32_t* prev_keep_idx, int32_t n_prev_keep,
+                       float* scores, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+size_t zr_priority_workspace_bytes(int32_t K, int32_t N, int mode);
+
+/* Eq. 1: pruning ratio gamma = (T_i - T_avg) / M_i from the task's iteration time,
+ * the average iteration time and the task's matrix-multiplication time; 0 when
+ * the task is not slower than the average; capped at gamma_max (< 1).  Pure host
+ * function; returns -1 on a non-positive M_i or a bad cap. */
+double zr_pruning_ratio(double T_i, double T_avg, double M_i, double gamma_max);
+
+/* Differentiated per-layer ratio (Sec. 3.2, Algorithm 1): zr_count_above writes
+ * L_uni = #{i : scores[i] > theta} to the DEVICE int32 `count` (one launch, async);
+ * zr_layer_ratio (pure host) returns max(1 - L_uni / L, alpha * gamma), or -1 on
+ * bad arguments.  theta = N_iter * theta_iter (1e-3 by default in the paper),
+ * alpha = 0.8 by default. */
+int zr_count_above(const float* scores, int32_t n, float theta, int32_t* count, void* stream);
+double zr_layer_ratio(int64_t count_above, int64_t L, double alpha, double gamma);
+
 /* Debugging aid: checks on the device that keep_idx[n_keep] is strictly
  * ascending and within [0, n).  SYNCHRONISES `stream`.  `flag` is a caller-owned
  * device int32 used as scratch.  Returns ZR_OK or ZR_ERR_INDEX. */

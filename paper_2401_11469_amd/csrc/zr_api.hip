@@ -260,6 +260,52 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     return ZR_OK;
 }
 
+int zr_priority_scores(const void* W_t, const void* W_prev, int64_t ld, int32_t K, int32_t N, int mode,
+                       const float* prev_scores, const int32_t* prev_keep_idx, int32_t n_prev_keep,
+                       float* scores, int dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!W_t || !W_prev || !scores) return ZR_ERR_NULL;
+    if (!valid_dtype(dtype)) return ZR_ERR_DTYPE;
+    if (!valid_mode(mode)) return ZR_ERR_MODE;
+    if (K < 1 || N < 1 || ld < N) return ZR_ERR_SHAPE;
+    if (prev_keep_idx) {
+        if (!prev_scores) return ZR_ERR_NULL;
+        const int32_t n = mode == ZR_DROP_N ? N : K;
+        if (n_prev_keep < 1 || n_prev_keep > n) return ZR_ERR_INDEX;
+    }
+    return launch_priority_scores(W_t, W_prev, ld, K, N, mode, prev_scores, prev_keep_idx, n_prev_keep, scores,
+                                  dtype, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t zr_priority_workspace_bytes(int32_t K, int32_t N, int mode)
+{
+    if (K < 1 || N < 1 || !valid_mode(mode)) return 0;
+    return priority_workspace_bytes(K, N, mode);
+}
+
+double zr_pruning_ratio(double T_i, double T_avg, double M_i, double gamma_max)
+{
+    if (!(M_i > 0.0) || !(gamma_max >= 0.0) || !(gamma_max < 1.0)) return -1.0;
+    const double g = (T_i - T_avg) / M_i;
+    if (!(g > 0.0)) return 0.0;          // not slower than the average (or NaN): prune nothing
+    return g < gamma_max ? g : gamma_max;
+}
+
+int zr_count_above(const float* scores, int32_t n, float theta, int32_t* count, void* stream)
+{
+    if (!scores || !count) return ZR_ERR_NULL;
+    if (n < 1) return ZR_ERR_SHAPE;
+    return launch_count_above(scores, n, theta, count, (hipStream_t)stream);
+}
+
+double zr_layer_ratio(int64_t count_above, int64_t L, double alpha, double gamma)
+{
+    if (L < 1 || count_above < 0 || count_above > L) return -1.0;
+    const double gk = 1.0 - (double)count_above / (double)L;
+    const double floor_ = alpha * gamma;
+    return gk > floor_ ? gk : floor_;
+}
+
 int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
               const int32_t* keep_idx, int32_t n_keep, int policy, const void* prev,
               int dtype, void* stream)

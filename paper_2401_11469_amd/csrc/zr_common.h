@@ -76,6 +76,11 @@ int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
                   int dtype, hipStream_t stream);
 int launch_compact_cols(const void* in, int64_t ld, int rows, int n, const int32_t* keep, int n_keep,
                         void* out, int64_t ldo, int width, hipStream_t stream);
+int launch_priority_scores(const void* Wt, const void* Wp, int64_t ld, int K, int N, int mode,
+                           const float* prev_scores, const int32_t* prev_keep, int n_prev_keep,
+                           float* scores, int dtype, void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t priority_workspace_bytes(int K, int N, int mode);
+int launch_count_above(const float* scores, int n, float theta, int32_t* count, hipStream_t stream);
 int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? ZR_OK : ZR_ERR_HIP; }

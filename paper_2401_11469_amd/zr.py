@@ -49,6 +49,17 @@ _lib.zr_extract_kept_columns.argtypes = [_vp, _i64, _i32, _i32, _vp, _i32, _vp, 
 _lib.zr_extract_kept_columns.restype = ctypes.c_int
 _lib.zr_debug_last_kernel.argtypes = []
 _lib.zr_debug_last_kernel.restype = ctypes.c_char_p
+_lib.zr_priority_scores.argtypes = [_vp, _vp, _i64, _i32, _i32, ctypes.c_int, _vp, _vp, _i32, _vp, ctypes.c_int,
+                                    _vp, ctypes.c_size_t, _vp]
+_lib.zr_priority_workspace_bytes.argtypes = [_i32, _i32, ctypes.c_int]
+_lib.zr_priority_workspace_bytes.restype = ctypes.c_size_t
+_lib.zr_priority_scores.restype = ctypes.c_int
+_lib.zr_pruning_ratio.argtypes = [_f64, _f64, _f64, _f64]
+_lib.zr_pruning_ratio.restype = _f64
+_lib.zr_count_above.argtypes = [_vp, _i32, ctypes.c_float, _vp, _vp]
+_lib.zr_count_above.restype = ctypes.c_int
+_lib.zr_layer_ratio.argtypes = [_i64, _i64, _f64, _f64]
+_lib.zr_layer_ratio.restype = _f64
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -207,6 +218,44 @@ def extract_kept_columns(inp: torch.Tensor, keep_idx: torch.Tensor, out: Optiona
     _check(_lib.zr_extract_kept_columns(ip, ld, rows, n, keep_idx.data_ptr(), keep_idx.numel(), op, ldo,
                                         _dtype_code(inp), _stream(stream)))
     return out
+
+
+def priority_scores(W_t: torch.Tensor, W_prev: torch.Tensor, mode: int,
+                    prev_scores: Optional[torch.Tensor] = None, prev_keep_idx: Optional[torch.Tensor] = None,
+                    scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                    stream=None) -> torch.Tensor:
+    K, N = W_t.shape
+    (tp, ld), (pp, ldp) = _mat(W_t, "W_t"), _mat(W_prev, "W_prev")
+    if W_prev.shape != W_t.shape or ldp != ld or W_prev.dtype != W_t.dtype:
+        raise ValueError("W_prev must match W_t in shape, leading dimension and dtype")
+    n = N if mode == DROP_N else K
+    if scores is None:
+        scores = torch.empty(n, dtype=torch.float32, device=W_t.device)
+    _check(_lib.zr_priority_scores(tp, pp, ld, K, N, mode,
+                                   None if prev_scores is None else prev_scores.data_ptr(),
+                                   None if prev_keep_idx is None else prev_keep_idx.data_ptr(),
+                                   0 if prev_keep_idx is None else prev_keep_idx.numel(),
+                                   scores.data_ptr(), _dtype_code(W_t), *_ws(workspace), _stream(stream)))
+    return scores
+
+
+def priority_workspace_bytes(K: int, N: int, mode: int) -> int:
+    return int(_lib.zr_priority_workspace_bytes(K, N, mode))
+
+
+def pruning_ratio(T_i: float, T_avg: float, M_i: float, gamma_max: float = 0.9) -> float:
+    return float(_lib.zr_pruning_ratio(T_i, T_avg, M_i, gamma_max))
+
+
+def count_above(scores: torch.Tensor, theta: float, count: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if count is None:
+        count = torch.empty(1, dtype=torch.int32, device=scores.device)
+    _check(_lib.zr_count_above(scores.data_ptr(), scores.numel(), float(theta), count.data_ptr(), _stream(stream)))
+    return count
+
+
+def layer_ratio(count_above_: int, L: int, alpha: float, gamma: float) -> float:
+    return float(_lib.zr_layer_ratio(int(count_above_), int(L), alpha, gamma))
 
 
 def debug_last_kernel() -> str:

@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared_symbols()
     assert {"zr_keep_count", "zr_resize_select", "zr_resized_linear_fwd", "zr_resized_linear_bwd",
             "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes",
-            "zr_extract_kept_columns", "zr_debug_last_kernel"} <= set(names)
+            "zr_extract_kept_columns", "zr_debug_last_kernel", "zr_priority_scores", "zr_pruning_ratio",
+            "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -57,6 +58,19 @@ def test_workspace_bytes_host_function(lib):
     assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2          # 2064 -> 2112
     assert f(8192, 4096, 3072, 2304, 0, 0) == 0                        # fp32: no workspace path
     assert f(0, 8, 8, 4, 0, 1) == 0
+
+
+def test_ratio_host_functions(lib):
+    f = lib.zr_pruning_ratio
+    f.argtypes = [ctypes.c_double] * 4
+    f.restype = ctypes.c_double
+    assert f(12.0, 10.0, 8.0, 0.9) == 0.25 and f(9.0, 10.0, 8.0, 0.9) == 0.0 and f(30.0, 10.0, 8.0, 0.9) == 0.9
+    assert f(1.0, 1.0, 0.0, 0.9) == -1.0 and f(2.0, 1.0, 1.0, 1.0) == -1.0 and f(float("nan"), 1.0, 1.0, 0.9) == 0.0
+    g = lib.zr_layer_ratio
+    g.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_double, ctypes.c_double]
+    g.restype = ctypes.c_double
+    assert g(4, 8, 0.8, 0.25) == 0.5 and g(4, 8, 0.8, 0.9) == 0.8 * 0.9 and g(0, 8, 0.8, 0.0) == 1.0
+    assert g(9, 8, 0.8, 0.0) == -1.0 and g(1, 0, 0.8, 0.0) == -1.0
 
 
 def test_status_strings(lib):

@@ -123,6 +123,57 @@ def test_validate_keep_idx(zr, torch_mod):
     assert not zr.validate_keep_idx(idx_gpu(torch, [-1, 3, 4]), 5)
 
 
+# ------------------------------------------- priority scores and ratios ---
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("use_ws", [False, True])
+@pytest.mark.parametrize("K,N", [(1, 1), (7, 5), (130, 257), (512, 256), (1000, 772), (2048, 1024)])
+def test_priority_scores_parity(zr, torch_mod, oracle, dtype, mode, K, N, use_ws):
+    torch = torch_mod
+    ws = None
+    if use_ws:
+        ws = torch.empty(max(16, zr.priority_workspace_bytes(K, N, mode)), dtype=torch.uint8, device="cuda")
+    g = np.random.Generator(np.random.PCG64(K * 7 + N))
+    cast = wl.round_to_bf16 if dtype == "bf16" else (lambda x: x)
+    Wp = cast((g.standard_normal((K, N)) * 0.02).astype(np.float32))
+    Wt = cast((Wp + g.standard_normal((K, N)).astype(np.float32) * 1e-3).astype(np.float32))
+    n = N if mode == DROP_N else K
+    prev_scores = g.random(n).astype(np.float32)
+    ld = N + 3 if N % 2 else N + 8          # odd shapes take the scalar loads, even ones the vector loads
+    Wtg, Wpg = to_gpu(torch, Wt, dtype, ld=ld), to_gpu(torch, Wp, dtype, ld=ld)
+    got = zr.priority_scores(Wtg, Wpg, mode, workspace=ws).cpu().numpy().astype(np.float64)
+    want = oracle.priority_scores(Wt, Wp, mode)
+    assert got.shape == want.shape
+    assert np.max(np.abs(got - want)) <= 1e-5 * max(np.max(np.abs(want)), 1e-30)
+    # incremental rule: previously pruned indices keep their previous score, bit for bit
+    keep = subset(3, n, max(1, (2 * n) // 3))
+    got = zr.priority_scores(Wtg, Wpg, mode, torch.from_numpy(prev_scores).cuda(), idx_gpu(torch, keep), workspace=ws)
+    got = got.cpu().numpy()
+    want = oracle.priority_scores(Wt, Wp, mode, prev_scores, keep)
+    dropped = np.setdiff1d(np.arange(n), keep)
+    assert np.array_equal(got[dropped], prev_scores[dropped])
+    assert np.max(np.abs(got[keep].astype(np.float64) - want[keep])) <= 1e-5 * max(np.max(np.abs(want)), 1e-30)
+    # bitwise repeatable
+    again = zr.priority_scores(Wtg, Wpg, mode, torch.from_numpy(prev_scores).cuda(), idx_gpu(torch, keep),
+                               workspace=ws).cpu().numpy()
+    assert np.array_equal(got, again)
+
+
+def test_ratio_controller_parity(zr, torch_mod, oracle):
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(77))
+    for n in (1, 63, 1000, 4096, 20000):
+        s = g.random(n).astype(np.float32)
+        for theta in (-1.0, 0.0, 0.25, float(s[0]), 2.0):
+            cnt = int(zr.count_above(torch.from_numpy(s).cuda(), theta).item())
+            assert cnt == int(np.count_nonzero(s > np.float32(theta)))
+            for gamma in (0.0, 0.3):
+                assert zr.layer_ratio(cnt, n, 0.8, gamma) == oracle.layer_ratio(s, np.float32(theta), 0.8, gamma)
+    for T_i, T_avg, M_i in ((12.0, 10.0, 8.0), (9.0, 10.0, 8.0), (30.0, 10.0, 8.0), (10.5, 10.0, 3.0)):
+        assert zr.pruning_ratio(T_i, T_avg, M_i) == oracle.pruning_ratio(T_i, T_avg, M_i)
+
+
 # ------------------------------------------------------------------ impute ---
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
