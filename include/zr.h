@@ -96,13 +96,18 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
 
 /* Size of the optional scratch buffer of the forward / backward calls below.
  * With a DEVICE buffer of at least this many bytes (16-byte aligned) the calls
- * first extract the kept columns of the ACTIVATION they gather along its
- * contiguous axis (X[:,S] for DROP_K, dY[:,S] for DROP_N: the paper's
- * "pruned_input", Sec. 3.1) into it, [M x n_keep rounded up to 64] bf16, zero
- * padded, and then run the products on ordinary loads; the weight shard is never
- * copied.  Without it (NULL, or too small) every gather is done in flight by
- * the GEMM loaders; results are the same to the last bit either way.  Returns 0
- * when no call would use a workspace (fp32).  Pure host function. */
+ * first extract the kept columns of every operand they would otherwise gather
+ * along its contiguous axis (Sec. 3.1: the remaining columns are concatenated)
+ * into it, [rows x n_keep rounded up to 64] bf16, zero padded, and then run the
+ * products on ordinary loads:
+ *   DROP_K: X[:,S] [M x w]                       (forward, dW)
+ *   DROP_N: dY[:,S] [M x w] (dX, dW), then W[:,S] [K x w] (forward at offset 0; dX
+ *           behind the extracted dY)
+ * Rows of W (DROP_K) are contiguous and are never copied.  A buffer that holds
+ * only the first part is used for that part.  Without it (NULL, or too small)
+ * every gather is done in flight by the GEMM loaders; results are the same to
+ * the last bit either way.  Returns 0 when no call would use a workspace
+ * (fp32).  Pure host function. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
 /* The extraction step on its own (Sec. 3.1: the remaining columns of the input
@@ -126,7 +131,7 @@ int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
  *  workspace / workspace_bytes: optional scratch, see zr_workspace_bytes; its
  *  contents are undefined afterwards; calls that share one must be ordered on
  *  one stream.
- *  Launches: 1 for ZERO (+1 with a workspace in DROP_K); +1 for AVERAGE / SAME.
+ *  Launches: 1 for ZERO (+1 with a workspace); +1 for AVERAGE / SAME.
  *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE, POLICY, LIMIT, HIP. */
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,

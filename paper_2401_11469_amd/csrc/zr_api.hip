@@ -67,9 +67,11 @@ extern "C" {
 
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype)
 {
-    (void)K; (void)N; (void)mode;
-    if (dtype != ZR_BF16 || M < 1 || n_keep < 1) return 0;
-    return (size_t)M * (size_t)round_up64(n_keep) * 2;
+    (void)N;
+    if (dtype != ZR_BF16 || M < 1 || K < 1 || n_keep < 1) return 0;
+    // extracted activation columns [M x width], then (DROP_N) extracted weight columns [K x width]
+    const size_t width = (size_t)round_up64(n_keep);
+    return (size_t)M * width * 2 + (mode == ZR_DROP_N ? (size_t)K * width * 2 : 0);
 }
 
 const char* zr_status_string(int status)
@@ -163,7 +165,14 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     }
     // Y[m,S[j]] = sum_k X[m,k] * W[k,S[j]], dropped columns imputed
     d.A = operand(X, ldx, true, nullptr, nullptr, M, K);
-    d.B = operand(W, ldw, false, nullptr, S, K, N);
+    const Extract ew = plan_extract(W, ldw, K, N, n_keep, dtype, workspace, workspace_bytes);
+    if (ew.use) {
+        st = launch_compact_cols(W, ldw, K, N, keep_idx, n_keep, workspace, ew.width, ew.width, s);
+        if (st != ZR_OK) return st;
+        d.B = operand(workspace, ew.width, false, nullptr, nullptr, K, ew.width);
+    } else {
+        d.B = operand(W, ldw, false, nullptr, S, K, N);
+    }
     d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
     st = launch_gemm(d, s);
     if (st != ZR_OK || full || policy == ZR_IMPUTE_ZERO) return st;
@@ -224,7 +233,20 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             } else {
                 d.A = operand(dY, lddy, true, nullptr, S, M, N);
             }
-            d.B = operand(W, ldw, true, nullptr, S, K, N);
+            // W[:,S] goes behind the extracted dY[:,S] when the scratch buffer holds both
+            Extract ew{false, 0};
+            if (ex.use) {
+                const size_t used = (size_t)M * (size_t)ex.width * 2;
+                ew = plan_extract(W, ldw, K, N, n_keep, dtype, (char*)workspace + used, workspace_bytes - used);
+                if (ew.use) {
+                    st = launch_compact_cols(W, ldw, K, N, keep_idx, n_keep, (char*)workspace + used, ew.width,
+                                             ew.width, s);
+                    if (st != ZR_OK) return st;
+                    d.B = operand((char*)workspace + used, ew.width, true, nullptr, nullptr, K, ew.width);
+                    d.B.zero_padded = true;
+                }
+            }
+            if (!ew.use) d.B = operand(W, ldw, true, nullptr, S, K, N);
             d.J = K; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = K;
         }
         st = launch_gemm(d, s);

@@ -54,8 +54,8 @@ def test_workspace_bytes_host_function(lib):
     f = lib.zr_workspace_bytes
     f.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_int, ctypes.c_int]
     f.restype = ctypes.c_size_t
-    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2          # 2304 is a multiple of 64
-    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2          # 2064 -> 2112
+    assert f(8192, 4096, 3072, 2304, 0, 1) == (8192 + 4096) * 2304 * 2   # DROP_N: dY[:,S] and W[:,S]; 2304 = 36 * 64
+    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2            # DROP_K: X[:,S] only; 2064 -> 2112
     assert f(8192, 4096, 3072, 2304, 0, 0) == 0                        # fp32: no workspace path
     assert f(0, 8, 8, 4, 0, 1) == 0
 
