@@ -118,21 +118,28 @@ def main() -> int:
                 zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
                 zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws)
             else:
-                # one event pair per product; a call that first extracts the kept
-                # activation columns into the scratch buffer (a second, HBM-bound
-                # kernel) is charged only the GEMM: the same extraction is timed
-                # on its own right before and subtracted
+                # one event pair per product; a call that first extracts kept columns
+                # into the scratch buffer (HBM-bound copy kernels) is charged only the
+                # GEMM: the same extractions are timed on their own right before and
+                # subtracted
                 fl = 2.0 * M * pr.K * pr.N * keep.numel() / p["n"]
                 ev = lambda: torch.cuda.Event(enable_timing=True)
+                width = (keep.numel() + 63) // 64 * 64
                 for op in ("fwd", "dX", "dW"):
-                    extracts = ws is not None and not full and (
-                        (pr.mode == zr.DROP_K and op in ("fwd", "dW")) or (pr.mode == zr.DROP_N and op in ("dX", "dW")))
+                    srcs = []
+                    if ws is not None and not full:
+                        if pr.mode == zr.DROP_K and op in ("fwd", "dW"):
+                            srcs = [p["X"]]
+                        elif pr.mode == zr.DROP_N:
+                            srcs = {"fwd": [p["W"]], "dX": [p["dY"], p["W"]], "dW": [p["dY"]]}[op]
                     x0, x1, e0, e1 = ev(), ev(), ev(), ev()
-                    if extracts:
-                        src = p["X"] if pr.mode == zr.DROP_K else p["dY"]
-                        width = (keep.numel() + 63) // 64 * 64
+                    if srcs:
                         x0.record()
-                        zr.extract_kept_columns(src, keep, out=ws[:M * width * 2].view(tdt).view(M, width))
+                        off = 0
+                        for src in srcs:
+                            rows = src.shape[0]
+                            zr.extract_kept_columns(src, keep, out=ws[off:off + rows * width * 2].view(tdt).view(rows, width))
+                            off += rows * width * 2
                         x1.record()
                     e0.record()
                     if op == "fwd":
@@ -142,7 +149,7 @@ def main() -> int:
                     else:
                         zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False, workspace=ws)
                     e1.record()
-                    events.append((zr.debug_last_kernel(), fl, e0, e1, (x0, x1) if extracts else None))
+                    events.append((zr.debug_last_kernel(), fl, e0, e1, (x0, x1, len(srcs)) if srcs else None))
 
     ratios = wl.ratio_sequence(args.config, args.warmup + args.steps)
 
@@ -178,7 +185,7 @@ def main() -> int:
         if xe is not None:
             x = xe[0].elapsed_time(xe[1])
             extract_ms += x
-            n_extract += 1
+            n_extract += xe[2]
             ms = max(ms - x, 0.0)
         d[0] += 1
         d[1] += fl
@@ -308,7 +315,7 @@ def main() -> int:
                                + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
                                + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
                    "path": "resize_select + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
-                           "with the optional scratch buffer for extracted activation columns"},
+                           "with the optional scratch buffer for the extracted kept columns of activations and weights"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "extract": extract, "by_ratio": sweep, "aux": aux,

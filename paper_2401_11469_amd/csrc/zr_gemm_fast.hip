@@ -527,26 +527,32 @@ struct DmaP {
 // chunk index XORed by 2 * (c & 3); fragments are read with the transposing
 // ds_read_tr16_b64, which hands a lane 4 consecutive c of ONE column out of a
 // 4 (c) x 16 (columns) block read by its 16-lane group.
+// A tile width R that is not a power of two (192) keeps the LDS geometry of the
+// next power of two RP: the lanes of the chunks beyond R are switched off, their
+// LDS slots stay unwritten and are never read.
 template <int R, int NT>
 struct DmaQ {
     static constexpr const char* NAME = "DmaQ";
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
-    static constexpr int WORDS = BK * R / 2;
+    static constexpr int RP = R <= 128 ? 128 : 256;
+    static constexpr int WORDS = BK * RP / 2;
     static constexpr int NW = NT / 64;
-    static constexpr int CPR = R / 8;            // chunks per row
+    static constexpr int CPR = RP / 8;           // chunk slots per row
     static constexpr int RPI = 64 / CPR;         // rows per instruction
     static constexpr int N = CPR / NW;           // instructions per wavefront per tile
     static_assert(CPR % NW == 0 && N >= 1 && 64 % CPR == 0, "tile does not split over the wavefronts");
+    static_assert(R % 64 == 0 && R <= RP && R > RP / 2, "unsupported tile width");
     const E* colp[N];
     int rr[N];                                    // memory row of the NEXT issue
+    bool active_;                                 // this lane's chunk lies inside the tile
 
     struct Reader {
         int rowbase, coloff[4];
         __device__ __forceinline__ void setup(int w0, int lane)
         {
             const int t16 = lane & 15;
-            rowbase = (8 * (lane >> 5) + (t16 >> 2)) * (R / 2);
+            rowbase = (8 * (lane >> 5) + (t16 >> 2)) * (RP / 2);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int col = w0 + t * 32 + 16 * ((lane >> 4) & 1) + 4 * (t16 & 3);
@@ -556,10 +562,10 @@ struct DmaQ {
         __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
         {
             typedef __attribute__((address_space(3))) v4i16* lp;
-            const uint32_t* p = stage + 16 * step * (R / 2) + rowbase + coloff[t];
+            const uint32_t* p = stage + 16 * step * (RP / 2) + rowbase + coloff[t];
             union { v4i16 h[2]; bf16x8 b; } x;
             x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
-            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (R / 2)));
+            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (RP / 2)));
             return x.b;
         }
     };
@@ -577,6 +583,8 @@ struct DmaQ {
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
+        // the swizzle below only permutes chunks inside aligned groups of 8
+        active_ = ((tid & 63) % CPR) * 8 < R;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
             const int chunk = ((tid & 63) % CPR) ^ (2 * (tile_row(q, tid) & 3));
@@ -587,9 +595,11 @@ struct DmaQ {
     __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
     {
         const int wave = tid >> 6;
+        if (R == RP || active_) {
 #pragma unroll
-        for (int q = 0; q < N; ++q)
-            dma16(colp[q] + (size_t)rr[q] * (size_t)op.ld, stage + (wave + NW * q) * 256);
+            for (int q = 0; q < N; ++q)
+                dma16(colp[q] + (size_t)rr[q] * (size_t)op.ld, stage + (wave + NW * q) * 256);
+        }
         rows_for(op, c0 + BK, C, tid);
     }
 };
@@ -874,7 +884,17 @@ int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
 struct Sched {
     int big_i_end, big_j_end;   // big tiles cover [0, big_i_end) x [0, big_j_end); 0 = no big panel
     bool cut_rows;              // the remainder panel is rows [big_i_end, I) (else columns [big_j_end, J))
+    double cost;                // estimate, in big-tile rounds
 };
+
+// One grid of 256 x 192 (or 192 x 256) tiles: three quarters of the MFMA work of a
+// big tile but 0.84 of its LDS traffic, which is what bounds the loop.  Only the
+// direct-to-LDS loaders have this shape.
+#ifndef ZR_COST_192
+#define ZR_COST_192 0.85
+#endif
+inline int64_t tiles_of(int I, int J, int bm, int bn) { return (int64_t)((I + bm - 1) / bm) * ((J + bn - 1) / bn); }
+inline double cost_192(int64_t tiles) { return ZR_COST_192 * (double)((tiles + 255) / 256); }
 
 inline double small_cost(int64_t ts)
 {
@@ -888,24 +908,25 @@ inline Sched plan_tiles(int I, int J)
     const int ti = (I + 255) / 256, tj = (J + 255) / 256;
     const int64_t T = (int64_t)ti * tj;
     auto smalls = [](int rows, int cols) { return (int64_t)((rows + 127) / 128) * ((cols + 127) / 128); };
-    Sched best{I, J, true};
+    Sched best{I, J, true, 0.0};
     double best_cost = (double)((T + 255) / 256);                  // all big
     {
         const double c = small_cost(smalls(I, J));                 // all small
-        if (c < best_cost) { best_cost = c; best = Sched{0, 0, true}; }
+        if (c < best_cost) { best_cost = c; best = Sched{0, 0, true, 0.0}; }
     }
     for (int q = 1; q * 256 < T; ++q) {                            // q full rounds of big tiles
         const int rb = (int)((int64_t)q * 256 / tj);               // big tile-rows
         if (rb >= 1 && rb < ti) {
             const double c = (double)(((int64_t)rb * tj + 255) / 256) + small_cost(smalls(I - rb * 256, J));
-            if (c < best_cost) { best_cost = c; best = Sched{rb * 256, J, true}; }
+            if (c < best_cost) { best_cost = c; best = Sched{rb * 256, J, true, 0.0}; }
         }
         const int cb = (int)((int64_t)q * 256 / ti);               // big tile-columns
         if (cb >= 1 && cb < tj) {
             const double c = (double)(((int64_t)cb * ti + 255) / 256) + small_cost(smalls(I, J - cb * 256));
-            if (c < best_cost) { best_cost = c; best = Sched{I, cb * 256, false}; }
+            if (c < best_cost) { best_cost = c; best = Sched{I, cb * 256, false, 0.0}; }
         }
     }
+    best.cost = best_cost;
     return best;
 }
 
@@ -913,6 +934,15 @@ template <template <int, int> class LA, template <int, int> class LB>
 int launch_shape(const FArgs& a, hipStream_t stream)
 {
     const Sched sc = plan_tiles(a.I, a.J);
+    if constexpr (LA<256, 512>::DMA && LB<256, 512>::DMA) {
+        const int64_t tj = tiles_of(a.I, a.J, 256, 192), ti = tiles_of(a.I, a.J, 192, 256);
+        const double cj = cost_192(tj), ci = cost_192(ti);
+        if (std::min(cj, ci) < sc.cost - 1e-9) {
+            // equal rounds: the grid with fewer tiles has less padding
+            if (cj < ci || (cj == ci && tj <= ti)) return launch_tile<LA, LB, 256, 192, 4, 2>(a, 0, a.I, 0, a.J, stream);
+            return launch_tile<LA, LB, 192, 256, 2, 4>(a, 0, a.I, 0, a.J, stream);
+        }
+    }
     if (sc.big_i_end == 0)                     // everything on small tiles
         return launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, 0, a.J, stream);
     int st = launch_tile<LA, LB, 256, 256, ZR_BIG_WM, ZR_BIG_WN>(a, 0, sc.big_i_end, 0, sc.big_j_end, stream);
