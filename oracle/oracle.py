@@ -32,6 +32,12 @@ Readings of the paper taken here (the paper is silent or ambiguous):
     element-wise mean of the kept slices of the current result.
     Average: parity unpinned against the paper (it prints no value for it);
     pinned only against this stated definition.
+  * lightweight migration (Sec. 4.1-4.2): the renumbering r' = (r_i + e - r_k) % e
+    and the range [m (r'-1), m r' - 1] are the paper's; when e - 1 does not
+    divide L_mig (the paper assumes it does), m = floor(L_mig / (e-1)) and the
+    first L_mig mod (e-1) renumbered receivers take one column more, so that
+    the ranges still tile [0, L_mig).  The straggler itself (r' = 0) computes
+    none of its migrated columns.
 """
 from __future__ import annotations
 
@@ -306,3 +312,34 @@ def resized_linear_bwd(X, W, dY, keep_idx, mode: int, policy: int = ZERO,
         dW = impute(_recover(pruned_dW, (K, N), 1, S), 1, S, policy, prev_dW)
         return dX, dW
     raise ValueError("mode")
+
+
+# ---------------------------------------------------------------------------
+# Lightweight migration, one receiver's share (Sec. 4.1, Sec. 4.2 renumbering)
+# ---------------------------------------------------------------------------
+
+def migration_range(r_i: int, r_k: int, e: int, L_mig: int) -> Tuple[int, int]:
+    """Columns of the straggler's L_mig migrated columns that task r_i computes,
+    as (begin, end) with end exclusive.  The straggler has rank r_k among e
+    tasks; the normal tasks are renumbered r' = (r_i + e - r_k) % e = 1..e-1
+    and task r' takes [m (r'-1), m r' - 1], m = L_mig / (e-1)."""
+    assert e >= 2 and L_mig >= 0
+    r_new = (r_i + e - r_k) % e
+    if r_new == 0:
+        return 0, 0
+    m, rem = divmod(L_mig, e - 1)
+    begin = m * (r_new - 1) + min(r_new - 1, rem)
+    count = m + (1 if r_new - 1 < rem else 0)
+    return begin, begin + count
+
+
+def migrated_accumulate(out, A, B, b_transposed: bool) -> np.ndarray:
+    """Local reduce of a migrated sub-matrix (Sec. 4.1): the receiver adds the
+    product of the slices it was assigned to its own partial-sum output,
+    out + A B (row-parallel forward: A = X_mig[:, range], B = W_mig[range, :])
+    or out + A B^T (column-parallel backward: A = dY_mig[:, range],
+    B = W_mig[:, range]), so that the ordinary all-reduce that follows also
+    carries the migrated results."""
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    return np.asarray(out, dtype=np.float64) + matmul(A, B.T if b_transposed else B)

@@ -454,3 +454,71 @@ def test_bf16_rounding_is_nearest_even():
     t = wl.make_tensors(2, 1, M=4)
     for v in t.values():
         assert np.array_equal(wl.round_to_bf16(v), v)
+
+
+# ---------------------------------------------------------------------------
+# Lightweight migration (Sec. 4.1 / 4.2)
+# ---------------------------------------------------------------------------
+
+def test_renumbering_matches_the_papers_worked_example(oracle):
+    path = os.path.join(os.path.dirname(__file__), "golden", "fig3_renumbering.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 2
+    for e, r_k, L_mig, r_i, new_rank, first, last in (map(int, r) for r in rows):
+        assert (r_i + e - r_k) % e == new_rank
+        assert oracle.migration_range(r_i, r_k, e, L_mig) == (first, last + 1)
+
+
+def test_migration_ranges_tile_the_migrated_columns(oracle):
+    """Brute force: for every straggler rank the receivers' ranges are disjoint,
+    in renumbered order, cover [0, L_mig) and differ in size by at most one;
+    with e-1 | L_mig every size is the paper's m."""
+    for e in range(2, 9):
+        for r_k in range(e):
+            for L_mig in range(0, 40):
+                assert oracle.migration_range(r_k, r_k, e, L_mig) == (0, 0)      # the straggler computes none
+                order = sorted((r for r in range(e) if r != r_k), key=lambda r: (r + e - r_k) % e)
+                pos, sizes = 0, []
+                for r in order:
+                    b, en = oracle.migration_range(r, r_k, e, L_mig)
+                    assert b == pos and en >= b
+                    sizes.append(en - b)
+                    pos = en
+                assert pos == L_mig
+                assert max(sizes) - min(sizes) <= 1
+                if L_mig % (e - 1) == 0:
+                    assert set(sizes) == {L_mig // (e - 1)}
+
+
+def test_merged_local_reduce_equals_the_stragglers_own_product(oracle):
+    """Integer-valued inputs (exact in float64): adding every receiver's slice
+    product into the partial sums gives what the straggler would have produced
+    for its migrated columns, for both layouts."""
+    g = np.random.Generator(np.random.PCG64(11))
+    e, r_k, L_mig, M, N = 4, 2, 10, 7, 5
+    A = g.integers(-4, 5, size=(M, L_mig)).astype(np.float64)      # X_mig or dY_mig
+    W_rows = g.integers(-4, 5, size=(L_mig, N)).astype(np.float64)  # W_mig[range, :]
+    base = g.integers(-9, 10, size=(M, N)).astype(np.float64)
+    for transposed in (False, True):
+        B_full = W_rows.T.copy() if transposed else W_rows           # [N x L] when transposed
+        total = base.copy()
+        for r in range(e):
+            b, en = oracle.migration_range(r, r_k, e, L_mig)
+            if en == b:
+                continue
+            Bs = B_full[:, b:en] if transposed else B_full[b:en, :]
+            total = oracle.migrated_accumulate(total, A[:, b:en], Bs, transposed)
+        want = base + np.einsum("ml,ln->mn", A, W_rows)
+        assert np.array_equal(total, want)
+
+
+def test_migrated_accumulate_hand_example(oracle):
+    out = np.array([[1.0, 2.0], [3.0, 4.0]])
+    A = np.array([[1.0, 2.0, 0.0], [0.0, 1.0, -1.0]])
+    B = np.array([[1.0, 0.0], [2.0, 1.0], [0.0, 3.0]])
+    # A B = [[5, 2], [2, -2]]
+    assert np.array_equal(oracle.migrated_accumulate(out, A, B, False), [[6.0, 4.0], [5.0, 2.0]])
+    assert np.array_equal(oracle.migrated_accumulate(out, A, B.T.copy(), True), [[6.0, 4.0], [5.0, 2.0]])
+    # a transposed operand passed under the wrong flag must not go unnoticed
+    sq = np.array([[1.0, 2.0], [3.0, 4.0]])
+    assert not np.array_equal(oracle.migrated_accumulate(out, sq, sq, False), oracle.migrated_accumulate(out, sq, sq, True))
