@@ -131,7 +131,8 @@ int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
  *  workspace / workspace_bytes: optional scratch, see zr_workspace_bytes; its
  *  contents are undefined afterwards; calls that share one must be ordered on
  *  one stream.
- *  Launches: 1 for ZERO (+1 with a workspace); +1 for AVERAGE / SAME.
+ *  Launches: 1 for ZERO and SAME (both written by the product's own epilogue),
+ *  +1 with a workspace, +1 for AVERAGE.
  *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE, POLICY, LIMIT, HIP. */
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
@@ -200,6 +201,27 @@ double zr_pruning_ratio(double T_i, double T_avg, double M_i, double gamma_max);
  * alpha = 0.8 by default. */
 int zr_count_above(const float* scores, int32_t n, float theta, int32_t* count, void* stream);
 double zr_layer_ratio(int64_t count_above, int64_t L, double alpha, double gamma);
+
+/* Lightweight migration, one receiver's share (Sec. 4.1 and the renumbering
+ * passage of Sec. 4.2).
+ * zr_migration_range (pure host): of the straggler's L_mig migrated columns,
+ * task r_i computes [*begin, *end): with the straggler at rank r_k among e
+ * tasks, r' = (r_i + e - r_k) % e and the range is [m (r'-1), m r' - 1],
+ * m = L_mig / (e-1); a remainder is spread one column each over the first
+ * receivers; the straggler (r' = 0) gets the empty range.  Errors: NULL, SHAPE.
+ * zr_migrated_accumulate: the local reduce that replaces the global one:
+ *   out[M x N] += A[M x C] * B           (b_transposed = 0, B is [C x N]: row-parallel forward,
+ *                                          A = X_mig[:, range], B = W_mig[range, :])
+ *   out[M x N] += A[M x C] * B^T         (b_transposed = 1, B is [N x C]: column-parallel backward,
+ *                                          A = dY_mig[:, range], B = W_mig[:, range])
+ * A, B, out are DEVICE sub-matrix views (pointer to the first element of the
+ * range + leading dimension); the old value of out joins the fp32 accumulator
+ * before the single rounding to the output type.  One launch.  16-byte aligned
+ * views with leading dimensions that are multiples of 8 run on the fast path.
+ * Errors: NULL, DTYPE, SHAPE, HIP. */
+int zr_migration_range(int32_t r_i, int32_t r_k, int32_t e, int64_t L_mig, int64_t* begin, int64_t* end);
+int zr_migrated_accumulate(const void* A, int64_t lda, const void* B, int64_t ldb, int b_transposed,
+                           void* out, int64_t ldo, int32_t M, int32_t N, int32_t C, int dtype, void* stream);
 
 /* Debugging aid: checks on the device that keep_idx[n_keep] is strictly
  * ascending and within [0, n).  SYNCHRONISES `stream`.  `flag` is a caller-owned

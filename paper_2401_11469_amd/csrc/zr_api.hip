@@ -174,8 +174,9 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
         d.B = operand(W, ldw, false, nullptr, S, K, N);
     }
     d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
+    if (needs_prev) d.prev = prev_Y;            // Same: copied by the scatter epilogue itself
     st = launch_gemm(d, s);
-    if (st != ZR_OK || full || policy == ZR_IMPUTE_ZERO) return st;
+    if (st != ZR_OK || full || policy != ZR_IMPUTE_AVERAGE) return st;
     return launch_impute(Y, ldy, M, N, 1, keep_idx, n_keep, policy, prev_Y, dtype, s);
 }
 
@@ -202,7 +203,8 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     }
     hipStream_t s = (hipStream_t)stream;
     const int32_t* S = full ? nullptr : keep_idx;
-    const bool post = !full && policy != ZR_IMPUTE_ZERO;
+    const bool same = !full && policy == ZR_IMPUTE_SAME;       // fused into the scatter epilogues
+    const bool post = !full && policy == ZR_IMPUTE_AVERAGE;    // second pass over the output
 
     // one extraction serves both products: X[:,S] (DROP_K, used by dW) or dY[:,S] (DROP_N)
     Extract ex{false, 0};
@@ -225,6 +227,7 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             d.A = operand(dY, lddy, true, nullptr, nullptr, M, N);
             d.B = operand(W, ldw, true, S, nullptr, K, N);
             d.J = n_keep; d.C = N; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = K;
+            if (same) d.prev = prev_dX;
         } else {
             // dX[m,k] = sum_{c<n'} dY[m,S[c]] * W[k,S[c]]
             if (ex.use) {
@@ -258,6 +261,7 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     }
     if (dW) {
         d.out = dW; d.ldo = lddw; d.C = M;
+        d.prev = same ? prev_dW : nullptr;
         if (mode == ZR_DROP_K) {
             // dW[S[i],n] = sum_m X[m,S[i]] * dY[m,n], dropped rows imputed
             if (ex.use) d.A = operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width);
@@ -326,6 +330,38 @@ double zr_layer_ratio(int64_t count_above, int64_t L, double alpha, double gamma
     const double gk = 1.0 - (double)count_above / (double)L;
     const double floor_ = alpha * gamma;
     return gk > floor_ ? gk : floor_;
+}
+
+int zr_migration_range(int32_t r_i, int32_t r_k, int32_t e, int64_t L_mig, int64_t* begin, int64_t* end)
+{
+    if (!begin || !end) return ZR_ERR_NULL;
+    if (e < 2 || r_i < 0 || r_k < 0 || L_mig < 0) return ZR_ERR_SHAPE;
+    const int64_t r_new = ((int64_t)r_i + e - r_k) % e;
+    if (r_new == 0) { *begin = 0; *end = 0; return ZR_OK; }      // the straggler itself
+    const int64_t m = L_mig / (e - 1), rem = L_mig % (e - 1);
+    const int64_t b = m * (r_new - 1) + std::min<int64_t>(r_new - 1, rem);
+    *begin = b;
+    *end = b + m + (r_new - 1 < rem ? 1 : 0);
+    return ZR_OK;
+}
+
+int zr_migrated_accumulate(const void* A, int64_t lda, const void* B, int64_t ldb, int b_transposed,
+                           void* out, int64_t ldo, int32_t M, int32_t N, int32_t C, int dtype, void* stream)
+{
+    if (!A || !B || !out) return ZR_ERR_NULL;
+    if (!valid_dtype(dtype)) return ZR_ERR_DTYPE;
+    if (M < 1 || N < 1 || C < 1) return ZR_ERR_SHAPE;
+    if (lda < C || ldo < N || ldb < (b_transposed ? C : N)) return ZR_ERR_SHAPE;
+    GemmDesc d;
+    d.dtype = dtype;
+    d.out = out; d.ldo = ldo; d.keep_idx = nullptr; d.out_full = N;
+    d.I = M; d.J = N; d.C = C; d.epilogue = EPI_PLAIN;
+    d.accumulate = true;
+    d.A = operand(A, lda, true, nullptr, nullptr, M, C);
+    // out[m,n] += sum_c A[m,c] * B[c,n]   or   sum_c A[m,c] * B[n,c]
+    d.B = b_transposed ? operand(B, ldb, true, nullptr, nullptr, N, C)
+                       : operand(B, ldb, false, nullptr, nullptr, C, N);
+    return launch_gemm(d, (hipStream_t)stream);
 }
 
 int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,

@@ -64,6 +64,11 @@ struct GemmDesc {
     const int32_t* keep_idx;   // list used by the scatter epilogues
     int out_full;              // full extent of the scattered output axis
     int dtype;
+    // Same imputation fused into the scatter epilogues: dropped positions copy this
+    // tensor (laid out like `out`, may alias it) instead of receiving +0
+    const void* prev = nullptr;
+    // out = round(out + D) in fp32 (plain epilogue only): the local reduce of migrated work
+    bool accumulate = false;
 };
 
 extern char g_last_kernel[128];

@@ -48,6 +48,7 @@ template <> struct Ty<ZR_BF16> {
     static constexpr int CPAD = 8;      // C tile pitch padding (elements)
     static __device__ __forceinline__ uint32_t pack(const E* v) { return (uint32_t)v[0] | ((uint32_t)v[1] << 16); }
     static __device__ __forceinline__ E from_f32(float f) { return (E)f32_to_bf16_bits(f); }
+    static __device__ __forceinline__ float to_f32(E v) { return bf16_bits_to_f32(v); }
 };
 template <> struct Ty<ZR_F32> {
     typedef float E;
@@ -57,6 +58,7 @@ template <> struct Ty<ZR_F32> {
     static constexpr int CPAD = 4;
     static __device__ __forceinline__ uint32_t pack(const E* v) { return __float_as_uint(v[0]); }
     static __device__ __forceinline__ E from_f32(float f) { return f; }
+    static __device__ __forceinline__ float to_f32(E v) { return v; }
 };
 
 struct OpView {
@@ -77,6 +79,8 @@ struct KArgs {
     int out_full;
     int out_vec;            // output rows allow 16-byte stores
     int tiles_j;
+    const void* prev;       // Same imputation source (layout of out) or nullptr
+    int accumulate;         // add the old contents of out (plain epilogue)
 };
 
 // ---------------------------------------------------------------------------
@@ -425,6 +429,23 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    if (g.accumulate) {
+        // the accumulators start from the old contents of the output (one rounding
+        // at the end); done here, where no other registers are live yet
+        const int rows_in_tile = min(BM, g.I - i0), cols_in_tile = min(BN, g.J - j0);
+        const E* old = (const E*)g.out;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
+                    const int col = wc0 + b * 32 + l32;
+                    if (row < rows_in_tile && col < cols_in_tile)
+                        acc[a][b][r] = Ty<DT>::to_f32(old[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
+                }
+    }
 
     LA la;
     LB lb;
@@ -471,6 +492,10 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
     // ---- epilogue: accumulators -> C tile in LDS (output type) ---------------
     E* Cs = (E*)smem;
     int* sidx = (int*)(Cs + BM * CP);
+    const int rows_valid = min(BM, g.I - i0);
+    const int cols_valid = min(BN, g.J - j0);
+    E* out = (E*)g.out;
+    const E* prev = (const E*)g.prev;
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -480,9 +505,6 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
                 const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
                 Cs[row * CP + wc0 + b * 32 + l32] = Ty<DT>::from_f32(acc[a][b][r]);
             }
-    const int rows_valid = min(BM, g.I - i0);
-    const int cols_valid = min(BN, g.J - j0);
-    E* out = (E*)g.out;
     constexpr int VEC = 16 / (int)sizeof(E);
 
     if (g.epilogue == EPI_COL_SCATTER) {
@@ -499,8 +521,10 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
                 const int jj = lower_bound_lds(sidx, cols_valid, p);
                 const bool hit = jj < cols_valid && sidx[jj] == p;
                 E* o = out + (size_t)i0 * (size_t)g.ldo + p;
+                const E* pv = prev ? prev + (size_t)i0 * (size_t)g.ldo + p : nullptr;
                 for (int row = 0; row < rows_valid; ++row) {
-                    o[(size_t)row * (size_t)g.ldo] = hit ? Cs[row * CP + jj] : E(0);
+                    o[(size_t)row * (size_t)g.ldo] =
+                        hit ? Cs[row * CP + jj] : (pv ? pv[(size_t)row * (size_t)g.ldo] : E(0));
                 }
             }
         }
@@ -534,7 +558,8 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
             const int ii = lower_bound_lds(sidx, rows_valid, p);
             if (ii < rows_valid && sidx[ii] == p) continue;
             E* o = out + (size_t)p * (size_t)g.ldo + j0;
-            for (int j = lane; j < cols_valid; j += 64) o[j] = E(0);
+            const E* pv = prev ? prev + (size_t)p * (size_t)g.ldo + j0 : nullptr;
+            for (int j = lane; j < cols_valid; j += 64) o[j] = pv ? pv[j] : E(0);
         }
     }
 }
@@ -588,6 +613,7 @@ int launch_dt(const GemmDesc& d, hipStream_t stream)
     k.out = d.out; k.ldo = d.ldo; k.epilogue = d.epilogue; k.keep = d.keep_idx; k.out_full = d.out_full;
     k.out_vec = ((uintptr_t)d.out % 16 == 0) && (d.ldo % VEC == 0);
     k.tiles_j = 0;
+    k.prev = d.prev; k.accumulate = d.accumulate ? 1 : 0;
     const bool av = vec_ok(d.A), bv = vec_ok(d.B);
     if (d.A.c_contig && !d.B.c_contig) return launch_fmt<DT, true, false>(k, av, bv, stream);
     if (d.A.c_contig && d.B.c_contig) return launch_fmt<DT, true, true>(k, av, bv, stream);

@@ -103,6 +103,8 @@ struct FArgs {
     int epilogue;
     const int32_t* keep;
     int out_full;
+    const E* prev;          // Same imputation source (layout of out) or nullptr
+    int accumulate;         // add the old contents of out (plain epilogue)
     // sub-rectangle of D this launch covers, in elements (multiples of 256 except at
     // the far edges of D) and its tile grid
     int i_base, j_base, i_end, j_end;
@@ -740,6 +742,22 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    if (g.accumulate) {
+        // the accumulators start from the old contents of the output (one rounding
+        // at the end); done here, where no other registers are live yet
+        const int rows_in_tile = min(BM, g.I - i0), cols_in_tile = min(BN, g.J - j0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
+                    const int col = wc0 + b * 32 + l32;
+                    if (row < rows_in_tile && col < cols_in_tile)
+                        acc[a][b][r] = bf16_bits_to_f32(g.out[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
+                }
+    }
 
     LA la;
     LB lb;
@@ -774,6 +792,9 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 
     // ---- epilogue -------------------------------------------------------------
     E* Cs = (E*)smem;
+    const int rows_valid = min(BM, g.I - i0);
+    const int cols_valid = min(BN, g.J - j0);
+    E* out = g.out;
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -783,9 +804,6 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
                 Cs[row * CP + wc0 + b * 32 + l32] = to_bf16(acc[a][b][r]);
             }
-    const int rows_valid = min(BM, g.I - i0);
-    const int cols_valid = min(BN, g.J - j0);
-    E* out = g.out;
 
     if (g.epilogue == EPI_COL_SCATTER) {
         // The tile owns the original columns from its first kept column (0 for the
@@ -805,18 +823,39 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             r0 = k0 ? r0 : 0;
             r1 = k1 ? r1 : 0;
             E* o = out + (size_t)i0 * (size_t)g.ldo + p0;
+            if (!g.prev) {
+                // dropped positions receive +0
+                if (own0 && own1) {
+                    for (int row = 0; row < rows_valid; ++row) {
+                        const uint32_t v0 = k0 ? Cs[row * CP + r0] : 0u;
+                        const uint32_t v1 = k1 ? Cs[row * CP + r1] : 0u;
+                        *(uint32_t*)(o + (size_t)row * (size_t)g.ldo) = v0 | (v1 << 16);
+                    }
+                } else if (own0) {
+                    for (int row = 0; row < rows_valid; ++row)
+                        o[(size_t)row * (size_t)g.ldo] = k0 ? Cs[row * CP + r0] : E(0);
+                } else if (own1) {
+                    for (int row = 0; row < rows_valid; ++row)
+                        o[(size_t)row * (size_t)g.ldo + 1] = k1 ? Cs[row * CP + r1] : E(0);
+                }
+                continue;
+            }
+            // Same: dropped positions copy the previous tensor's value
+            const E* pv = g.prev + (size_t)i0 * (size_t)g.ldo + p0;
             if (own0 && own1) {
+                const bool need_prev = !(k0 && k1);
                 for (int row = 0; row < rows_valid; ++row) {
-                    const uint32_t v0 = k0 ? Cs[row * CP + r0] : 0u;
-                    const uint32_t v1 = k1 ? Cs[row * CP + r1] : 0u;
+                    const uint32_t old = need_prev ? *(const uint32_t*)(pv + (size_t)row * (size_t)g.ldo) : 0u;
+                    const uint32_t v0 = k0 ? Cs[row * CP + r0] : (old & 0xffffu);
+                    const uint32_t v1 = k1 ? Cs[row * CP + r1] : (old >> 16);
                     *(uint32_t*)(o + (size_t)row * (size_t)g.ldo) = v0 | (v1 << 16);
                 }
             } else if (own0) {
                 for (int row = 0; row < rows_valid; ++row)
-                    o[(size_t)row * (size_t)g.ldo] = k0 ? Cs[row * CP + r0] : E(0);
+                    o[(size_t)row * (size_t)g.ldo] = k0 ? Cs[row * CP + r0] : pv[(size_t)row * (size_t)g.ldo];
             } else if (own1) {
                 for (int row = 0; row < rows_valid; ++row)
-                    o[(size_t)row * (size_t)g.ldo + 1] = k1 ? Cs[row * CP + r1] : E(0);
+                    o[(size_t)row * (size_t)g.ldo + 1] = k1 ? Cs[row * CP + r1] : pv[(size_t)row * (size_t)g.ldo + 1];
             }
         }
         return;
@@ -841,7 +880,12 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             const int ii = lower_bound_lds(idxA, rows_valid, p);
             if (ii < rows_valid && idxA[ii] == p) continue;
             E* o = out + (size_t)p * (size_t)g.ldo + j0;
-            for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = zero4();
+            if (!g.prev) {
+                for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = zero4();
+            } else {
+                const E* pv = g.prev + (size_t)p * (size_t)g.ldo + j0;
+                for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = *(const uint4*)(pv + j);
+            }
         }
     }
 }
@@ -975,12 +1019,15 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     if (!chunked_ok(d.A) || !chunked_ok(d.B)) return -1;
     if (d.epilogue != EPI_COL_SCATTER && d.J % 8 != 0) return -1;
     if (d.I < 1 || d.J < 1 || d.C < 1) return -1;
+    if (d.prev && (uintptr_t)d.prev % 16 != 0) return -1;
+    if (d.accumulate && d.epilogue != EPI_PLAIN) return -1;
 
     FArgs a;
     a.A = FOp{(const E*)d.A.base, d.A.ld, d.A.map_strided, d.A.map_contig, d.A.n_strided, d.A.n_contig};
     a.B = FOp{(const E*)d.B.base, d.B.ld, d.B.map_strided, d.B.map_contig, d.B.n_strided, d.B.n_contig};
     a.I = d.I; a.J = d.J; a.C = d.C;
     a.out = (E*)d.out; a.ldo = d.ldo; a.epilogue = d.epilogue; a.keep = d.keep_idx; a.out_full = d.out_full;
+    a.prev = (const E*)d.prev; a.accumulate = d.accumulate ? 1 : 0;
     a.tiles_i = a.tiles_j = 0;
     a.i_base = a.j_base = a.i_end = a.j_end = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;

@@ -60,6 +60,10 @@ _lib.zr_count_above.argtypes = [_vp, _i32, ctypes.c_float, _vp, _vp]
 _lib.zr_count_above.restype = ctypes.c_int
 _lib.zr_layer_ratio.argtypes = [_i64, _i64, _f64, _f64]
 _lib.zr_layer_ratio.restype = _f64
+_lib.zr_migration_range.argtypes = [_i32, _i32, _i32, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
+_lib.zr_migration_range.restype = ctypes.c_int
+_lib.zr_migrated_accumulate.argtypes = [_vp, _i64, _vp, _i64, ctypes.c_int, _vp, _i64, _i32, _i32, _i32, ctypes.c_int, _vp]
+_lib.zr_migrated_accumulate.restype = ctypes.c_int
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -256,6 +260,26 @@ def count_above(scores: torch.Tensor, theta: float, count: Optional[torch.Tensor
 
 def layer_ratio(count_above_: int, L: int, alpha: float, gamma: float) -> float:
     return float(_lib.zr_layer_ratio(int(count_above_), int(L), alpha, gamma))
+
+
+def migration_range(r_i: int, r_k: int, e: int, L_mig: int):
+    b, en = _i64(0), _i64(0)
+    _check(_lib.zr_migration_range(r_i, r_k, e, L_mig, ctypes.byref(b), ctypes.byref(en)))
+    return int(b.value), int(en.value)
+
+
+def migrated_accumulate(out: torch.Tensor, A: torch.Tensor, B: torch.Tensor, b_transposed: bool, stream=None) -> torch.Tensor:
+    """out += A @ B (or A @ B.T); A, B, out may be column/row slices of larger matrices."""
+    M, C = A.shape
+    N = out.shape[1]
+    if out.shape[0] != M or tuple(B.shape) != ((N, C) if b_transposed else (C, N)):
+        raise ValueError("shape mismatch")
+    if not (A.dtype == B.dtype == out.dtype):
+        raise ValueError("dtype mismatch")
+    (ap, lda), (bp, ldb), (op, ldo) = _mat(A, "A"), _mat(B, "B"), _mat(out, "out")
+    _check(_lib.zr_migrated_accumulate(ap, lda, bp, ldb, 1 if b_transposed else 0, op, ldo, M, N, C,
+                                       _dtype_code(out), _stream(stream)))
+    return out
 
 
 def debug_last_kernel() -> str:

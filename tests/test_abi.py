@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"zr_keep_count", "zr_resize_select", "zr_resized_linear_fwd", "zr_resized_linear_bwd",
             "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes",
             "zr_extract_kept_columns", "zr_debug_last_kernel", "zr_priority_scores", "zr_pruning_ratio",
-            "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes"} <= set(names)
+            "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes", "zr_migration_range",
+            "zr_migrated_accumulate"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -71,6 +72,22 @@ def test_ratio_host_functions(lib):
     g.restype = ctypes.c_double
     assert g(4, 8, 0.8, 0.25) == 0.5 and g(4, 8, 0.8, 0.9) == 0.8 * 0.9 and g(0, 8, 0.8, 0.0) == 1.0
     assert g(9, 8, 0.8, 0.0) == -1.0 and g(1, 0, 0.8, 0.0) == -1.0
+
+
+def test_migration_range_host_function(lib, oracle):
+    f = lib.zr_migration_range
+    f.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+    f.restype = ctypes.c_int
+    b, e_ = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    for e in range(2, 9):
+        for r_k in range(e):
+            for L_mig in (0, 1, 5, 6, 7, 24, 1000):
+                for r_i in range(e):
+                    assert f(r_i, r_k, e, L_mig, ctypes.byref(b), ctypes.byref(e_)) == 0
+                    assert (b.value, e_.value) == oracle.migration_range(r_i, r_k, e, L_mig)
+    assert f(2, 1, 3, 2, ctypes.byref(b), ctypes.byref(e_)) == 0 and (b.value, e_.value) == (0, 1)   # Fig. 3, task-2
+    assert f(0, 0, 1, 4, ctypes.byref(b), ctypes.byref(e_)) != 0
+    assert f(0, 0, 2, 4, None, ctypes.byref(e_)) != 0
 
 
 def test_status_strings(lib):

@@ -174,6 +174,61 @@ def test_ratio_controller_parity(zr, torch_mod, oracle):
         assert zr.pruning_ratio(T_i, T_avg, M_i) == oracle.pruning_ratio(T_i, T_avg, M_i)
 
 
+# ------------------------------------------ migrated share, local reduce ---
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("transposed", [False, True])
+@pytest.mark.parametrize("M,N,L,begin,end", [
+    (64, 64, 64, 0, 64),          # whole, aligned
+    (300, 264, 520, 128, 392),    # aligned slice spanning tiles (fast path for bf16)
+    (300, 264, 520, 131, 390),    # unaligned slice
+    (130, 77, 40, 3, 4),          # a single migrated column
+    (513, 1030, 300, 0, 300),     # several tiles with ragged edges
+])
+def test_migrated_accumulate_parity(zr, torch_mod, oracle, dtype, transposed, M, N, L, begin, end):
+    """out += A[:, range] @ W_rows[range, :] in both storage layouts of the weight."""
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(M + N + L + begin))
+    cast = wl.round_to_bf16 if dtype == "bf16" else (lambda x: x)
+    A = cast(g.standard_normal((M, L)).astype(np.float32))
+    Wm = cast((g.standard_normal((N, L) if transposed else (L, N)) * 0.05).astype(np.float32))
+    base = cast(g.standard_normal((M, N)).astype(np.float32))
+    Ag, Wg, out = to_gpu(torch, A, dtype), to_gpu(torch, Wm, dtype), to_gpu(torch, base, dtype, ld=N + 8)
+    As = Ag[:, begin:end]
+    Bs = Wg[:, begin:end] if transposed else Wg[begin:end, :]
+    zr.migrated_accumulate(out, As, Bs, transposed)
+    torch.cuda.synchronize()
+    assert torch.all(out._base[:, N:] == 777.0), "padding overwritten"
+    want = oracle.migrated_accumulate(base, A[:, begin:end], Wm[:, begin:end] if transposed else Wm[begin:end, :],
+                                      transposed)
+    err = np.linalg.norm(to_np(out) - want) / np.linalg.norm(want)
+    assert err <= TOL[dtype], err
+    # a second share lands on top of the first (the receiver may serve several stragglers)
+    zr.migrated_accumulate(out, As, Bs, transposed)
+    want2 = oracle.migrated_accumulate(want, A[:, begin:end], Wm[:, begin:end] if transposed else Wm[begin:end, :],
+                                       transposed)
+    err = np.linalg.norm(to_np(out) - want2) / np.linalg.norm(want2)
+    assert err <= 2 * TOL[dtype], err
+
+
+def test_migrated_shares_sum_to_the_stragglers_product(zr, torch_mod, oracle):
+    """fp32, integer-valued inputs (every sum exact): the receivers' shares, each
+    over its zr_migration_range, add up to the straggler's own product."""
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(99))
+    e, r_k, L_mig, M, N = 5, 3, 70, 96, 80
+    A = g.integers(-3, 4, size=(M, L_mig)).astype(np.float32)
+    W = g.integers(-3, 4, size=(L_mig, N)).astype(np.float32)
+    total = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    Ag, Wg = torch.from_numpy(A).cuda(), torch.from_numpy(W).cuda()
+    for r in range(e):
+        b, en = zr.migration_range(r, r_k, e, L_mig)
+        assert (b, en) == oracle.migration_range(r, r_k, e, L_mig)
+        if en > b:
+            zr.migrated_accumulate(total, Ag[:, b:en], Wg[b:en, :], False)
+    assert np.array_equal(total.cpu().numpy().astype(np.float64), A.astype(np.float64) @ W.astype(np.float64))
+
+
 # ------------------------------------------------------------------ impute ---
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -350,6 +405,30 @@ def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
             S = S.astype(np.int32)
             got = run_layer(zr, torch, case, S, mode, "bf16")
             check_layer(oracle, case, S, mode, "bf16", ZERO, got)
+            # Same: the scatter epilogue copies the previous tensor at the same positions
+            got = run_layer(zr, torch, case, S, mode, "bf16", SAME)
+            check_layer(oracle, case, S, mode, "bf16", SAME, got)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pad", [0, 3])
+def test_same_imputation_in_place(zr, torch_mod, oracle, dtype, pad):
+    """The previous tensor may be the output buffer itself: dropped positions
+    then keep what they held, kept positions receive the new results."""
+    torch = torch_mod
+    M, K, N = 300, 264, 392
+    case = wl.random_case(4242, M, K, N, dtype)
+    for mode in (DROP_N, DROP_K):
+        n = N if mode == DROP_N else K
+        S = subset(17, n, (2 * n) // 3)
+        keep = idx_gpu(torch, S)
+        ld = (lambda c: c + pad) if pad else (lambda c: None)
+        X, W, dY = (to_gpu(torch, case[k], dtype, ld(c)) for k, c in (("X", K), ("W", N), ("dY", N)))
+        Y, dX, dW = (to_gpu(torch, case[k], dtype, ld(c)) for k, c in (("prev_Y", N), ("prev_dX", K), ("prev_dW", N)))
+        zr.resized_linear_fwd(X, W, keep, mode, SAME, Y, Y=Y)
+        zr.resized_linear_bwd(X, W, dY, keep, mode, SAME, dX, dW, dX=dX, dW=dW)
+        torch.cuda.synchronize()
+        check_layer(oracle, case, S, mode, dtype, SAME, (to_np(Y), to_np(dX), to_np(dW)))
 
 
 @pytest.mark.parametrize("mode", [DROP_N, DROP_K])
