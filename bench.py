@@ -109,10 +109,12 @@ def main() -> int:
                                  zr.keep_count(p["n"], wl.ratio_for(cfg, p["pr"], ratio))) for p in projs)
 
     def run_step(ratio: float, events=None):
-        for p in projs:
+        # the step's selections: one launch for all projections of the shard
+        keeps, _ = zr.resize_select_multi([p["scores"] for p in projs],
+                                          [wl.ratio_for(cfg, p["pr"], ratio) for p in projs],
+                                          keep_idx=[p["keep"] for p in projs], drop_idx=[p["drop"] for p in projs])
+        for p, keep in zip(projs, keeps):
             pr = p["pr"]
-            r = wl.ratio_for(cfg, pr, ratio)
-            keep, _ = zr.resize_select(p["scores"], r, keep_idx=p["keep"], drop_idx=p["drop"])
             full = keep.numel() == p["n"]
             if events is None:
                 zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
@@ -314,7 +316,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: M={M} tokens, projections "
                                + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
                                + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
-                   "path": "resize_select + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
+                   "path": "resize_select_multi (one launch for the 5 projections) + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
                            "with the optional scratch buffer for the extracted kept columns of activations and weights"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,

@@ -94,6 +94,16 @@ int64_t zr_keep_count(int64_t n, double ratio);
 int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio,
                      int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, void* stream);
 
+/* The same selection for `count` (<= 16) independent score vectors of different
+ * lengths in ONE launch, e.g. all projections of a layer shard at the start of
+ * a step.  scores, n, ratio, keep_idx, drop_idx are HOST arrays of `count`
+ * entries; scores[b], keep_idx[b], drop_idx[b] are DEVICE pointers (drop_idx, or
+ * any drop_idx[b], may be NULL); keep_idx[b] holds zr_keep_count(n[b], ratio[b])
+ * entries, drop_idx[b] the rest.  The host arrays are read before the call
+ * returns.  Errors: NULL, SHAPE, RATIO, LIMIT (count > 16, n > 2^24). */
+int zr_resize_select_multi(int32_t count, const float* const* scores, const int32_t* n, const double* ratio,
+                           int32_t* const* keep_idx, int32_t* const* drop_idx, void* stream);
+
 /* Size of the optional scratch buffer of the forward / backward calls below.
  * With a DEVICE buffer of at least this many bytes (16-byte aligned) the calls
  * first extract the kept columns of every operand they would otherwise gather

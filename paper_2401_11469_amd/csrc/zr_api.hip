@@ -129,6 +129,28 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
     return launch_select(scores, n, batch, (int)n_keep, keep_idx, drop_idx, ld_idx, (hipStream_t)stream);
 }
 
+int zr_resize_select_multi(int32_t count, const float* const* scores, const int32_t* n, const double* ratio,
+                           int32_t* const* keep_idx, int32_t* const* drop_idx, void* stream)
+{
+    if (!scores || !n || !ratio || !keep_idx) return ZR_ERR_NULL;
+    if (count < 1) return ZR_ERR_SHAPE;
+    if (count > ZR_SELECT_MULTI_MAX) return ZR_ERR_LIMIT;
+    SelectMulti m;
+    for (int b = 0; b < count; ++b) {
+        if (!scores[b] || !keep_idx[b]) return ZR_ERR_NULL;
+        if (n[b] < 1) return ZR_ERR_SHAPE;
+        if (n[b] > (1 << 24)) return ZR_ERR_LIMIT;
+        const int64_t n_keep = zr_keep_count(n[b], ratio[b]);
+        if (n_keep < 1) return ZR_ERR_RATIO;
+        m.scores[b] = scores[b]; m.keep[b] = keep_idx[b]; m.drop[b] = drop_idx ? drop_idx[b] : nullptr;
+        m.n[b] = n[b]; m.n_keep[b] = (int)n_keep;
+    }
+    for (int b = count; b < ZR_SELECT_MULTI_MAX; ++b) {
+        m.scores[b] = nullptr; m.keep[b] = nullptr; m.drop[b] = nullptr; m.n[b] = 0; m.n_keep[b] = 0;
+    }
+    return launch_select_multi(m, count, (hipStream_t)stream);
+}
+
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,

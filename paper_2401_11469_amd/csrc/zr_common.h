@@ -76,6 +76,15 @@ int launch_gemm(const GemmDesc& d, hipStream_t stream);
 int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,
                   int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream);
+constexpr int ZR_SELECT_MULTI_MAX = 16;
+struct SelectMulti {
+    const float* scores[ZR_SELECT_MULTI_MAX];
+    int32_t* keep[ZR_SELECT_MULTI_MAX];
+    int32_t* drop[ZR_SELECT_MULTI_MAX];
+    int n[ZR_SELECT_MULTI_MAX];
+    int n_keep[ZR_SELECT_MULTI_MAX];
+};
+int launch_select_multi(const SelectMulti& m, int count, hipStream_t stream);
 int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
                   const int32_t* keep_idx, int n_keep, int policy, const void* prev,
                   int dtype, hipStream_t stream);

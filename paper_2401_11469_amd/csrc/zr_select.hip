@@ -32,10 +32,10 @@ __device__ __forceinline__ uint32_t order_key(float s)
 
 constexpr int SEL_LDS_KEYS = 12288;    // 48 KB of order keys
 
+// One workgroup selects one score vector s[n]: keep[n_keep] and drop[n - n_keep].
 template <bool STAGED>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
-    const float* __restrict__ scores, int n, int n_keep,
-    int32_t* __restrict__ keep_idx, int32_t* __restrict__ drop_idx, int64_t ld_idx)
+__device__ __forceinline__ void select_body(const float* __restrict__ s, int n, int n_keep,
+                                            int32_t* __restrict__ keep, int32_t* __restrict__ drop)
 {
     __shared__ uint32_t keys[STAGED ? SEL_LDS_KEYS : 1];
     __shared__ uint32_t hist[256];
@@ -45,9 +45,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const float* s = scores + (size_t)blockIdx.x * (size_t)n;
-    int32_t* keep = keep_idx + (size_t)blockIdx.x * (size_t)ld_idx;
-    int32_t* drop = drop_idx ? drop_idx + (size_t)blockIdx.x * (size_t)ld_idx : nullptr;
 
     if (STAGED) {
         for (int i = tid; i < n; i += SEL_THREADS) keys[i] = order_key(s[i]);
@@ -145,6 +142,26 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     }
 }
 
+template <bool STAGED>
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+    const float* __restrict__ scores, int n, int n_keep,
+    int32_t* __restrict__ keep_idx, int32_t* __restrict__ drop_idx, int64_t ld_idx)
+{
+    select_body<STAGED>(scores + (size_t)blockIdx.x * (size_t)n, n, n_keep,
+                        keep_idx + (size_t)blockIdx.x * (size_t)ld_idx,
+                        drop_idx ? drop_idx + (size_t)blockIdx.x * (size_t)ld_idx : nullptr);
+}
+
+// Several vectors of different lengths in one launch (the projections of a layer
+// shard): workgroup b takes descriptor b.  The descriptors travel as a kernel
+// argument, no device memory is involved.
+template <bool STAGED>
+__global__ __launch_bounds__(SEL_THREADS) void select_multi_kernel(const SelectMulti m)
+{
+    const int b = blockIdx.x;
+    select_body<STAGED>(m.scores[b], m.n[b], m.n_keep[b], m.keep[b], m.drop[b]);
+}
+
 __global__ void validate_kernel(const int32_t* __restrict__ keep_idx, int n_keep, int n,
                                 int32_t* __restrict__ flag)
 {
@@ -167,6 +184,17 @@ int launch_select(const float* scores, int n, int batch, int n_keep,
     else
         hipLaunchKernelGGL(select_kernel<false>, dim3(batch), dim3(SEL_THREADS), 0, stream,
                            scores, n, n_keep, keep_idx, drop_idx, ld_idx);
+    return hip_status(hipGetLastError());
+}
+
+int launch_select_multi(const SelectMulti& m, int count, hipStream_t stream)
+{
+    bool staged = true;
+    for (int b = 0; b < count; ++b) staged = staged && m.n[b] <= SEL_LDS_KEYS;
+    if (staged)
+        hipLaunchKernelGGL(select_multi_kernel<true>, dim3(count), dim3(SEL_THREADS), 0, stream, m);
+    else
+        hipLaunchKernelGGL(select_multi_kernel<false>, dim3(count), dim3(SEL_THREADS), 0, stream, m);
     return hip_status(hipGetLastError());
 }
 

@@ -64,6 +64,9 @@ _lib.zr_migration_range.argtypes = [_i32, _i32, _i32, _i64, ctypes.POINTER(_i64)
 _lib.zr_migration_range.restype = ctypes.c_int
 _lib.zr_migrated_accumulate.argtypes = [_vp, _i64, _vp, _i64, ctypes.c_int, _vp, _i64, _i32, _i32, _i32, ctypes.c_int, _vp]
 _lib.zr_migrated_accumulate.restype = ctypes.c_int
+_lib.zr_resize_select_multi.argtypes = [_i32, ctypes.POINTER(_vp), ctypes.POINTER(_i32), ctypes.POINTER(_f64),
+                                        ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]
+_lib.zr_resize_select_multi.restype = ctypes.c_int
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -153,6 +156,27 @@ def resize_select(scores: torch.Tensor, ratio: float, keep_idx: Optional[torch.T
         k = k[0]
         d = None if d is None else d[0]
     return k, d
+
+
+def resize_select_multi(scores, ratios, keep_idx=None, drop_idx=None, stream=None):
+    """One launch for several score vectors (lists of 1-D fp32 GPU tensors and ratios).
+    Returns lists of kept / dropped index tensors (views of the given buffers, or new ones)."""
+    cnt = len(scores)
+    ns = [int(s.numel()) for s in scores]
+    nk = [keep_count(n, r) for n, r in zip(ns, ratios)]
+    if keep_idx is None:
+        keep_idx = [torch.empty(n, dtype=torch.int32, device=s.device) for n, s in zip(ns, scores)]
+    if drop_idx is None:
+        drop_idx = [torch.empty(n, dtype=torch.int32, device=s.device) for n, s in zip(ns, scores)]
+    for s in scores:
+        if s.dtype != torch.float32 or not s.is_cuda or not s.is_contiguous():
+            raise ValueError("scores: contiguous fp32 GPU tensors")
+    PV, PI, PD = _vp * cnt, _i32 * cnt, _f64 * cnt
+    _check(_lib.zr_resize_select_multi(cnt, PV(*[s.data_ptr() for s in scores]), PI(*ns), PD(*[float(r) for r in ratios]),
+                                       PV(*[k.data_ptr() for k in keep_idx]), PV(*[d.data_ptr() for d in drop_idx]),
+                                       _stream(stream)))
+    return ([k.view(-1)[:c] for k, c in zip(keep_idx, nk)],
+            [d.view(-1)[:n - c] for d, n, c in zip(drop_idx, ns, nk)])
 
 
 def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor, mode: int,

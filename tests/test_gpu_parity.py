@@ -286,6 +286,26 @@ def test_extract_kept_columns_bit_exact(zr, torch_mod, oracle, rows, n):
         assert torch.all(out[:, width:] == 777.0)
 
 
+def test_select_multi_matches_single_vector_calls(zr, torch_mod, oracle):
+    """One launch over vectors of different lengths and ratios, including a
+    vector too long for the LDS-staged variant."""
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(321))
+    for ns, ratios in (([3072, 1024, 2752, 2752, 2752], [0.25] * 5),
+                       ([1, 7, 64, 1000, 4097, 777], [0.0, 0.5, 0.3, 0.999, 0.05, 0.45]),
+                       ([20000, 5], [0.1, 0.2])):
+        hs = []
+        for n in ns:
+            v = g.standard_normal(n).astype(np.float32)
+            v[g.integers(0, n, size=max(1, n // 10))] = 0.5          # ties
+            hs.append(v)
+        keeps, drops = zr.resize_select_multi([torch.from_numpy(v).cuda() for v in hs], ratios)
+        torch.cuda.synchronize()
+        for v, r, k, d in zip(hs, ratios, keeps, drops):
+            S, P = oracle.resize_select(v, r)
+            assert np.array_equal(k.cpu().numpy(), S) and np.array_equal(d.cpu().numpy(), P)
+
+
 # ------------------------------------------------------------------- GEMMs ---
 
 def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False):
