@@ -90,12 +90,17 @@ def main() -> int:
         t = wl.make_tensors(args.config, pi)
         scores = wl.make_scores(args.config, pi, t["W"])
         n = pr.n_axis
+        # Column-parallel shards (kept list on the output features) are stored [N x K]
+        # ([out, in]), row-parallel ones [K x N]: in both the kept list selects ROWS
+        # of the stored weight, which the GEMM loaders gather in flight (no weight copy).
+        nk = pr.mode == zr.DROP_N
+        Wd = torch.from_numpy(np.ascontiguousarray(t["W"].T) if nk else t["W"]).to(tdt).to(dev)
         projs.append(dict(
-            pr=pr, n=n,
-            X=torch.from_numpy(t["X"]).to(tdt).to(dev), W=torch.from_numpy(t["W"]).to(tdt).to(dev),
+            pr=pr, n=n, layout=zr.W_NK if nk else zr.W_KN,
+            X=torch.from_numpy(t["X"]).to(tdt).to(dev), W=Wd,
             dY=torch.from_numpy(t["dY"]).to(tdt).to(dev), scores=torch.from_numpy(scores).to(dev),
             Y=torch.empty((M, pr.N), dtype=tdt, device=dev), dX=torch.empty((M, pr.K), dtype=tdt, device=dev),
-            dW=torch.empty((pr.K, pr.N), dtype=tdt, device=dev),
+            dW=torch.empty(tuple(Wd.shape), dtype=tdt, device=dev),
             keep=torch.empty((1, n), dtype=torch.int32, device=dev),
             drop=torch.empty((1, n), dtype=torch.int32, device=dev)))
         del t
@@ -117,8 +122,9 @@ def main() -> int:
             pr = p["pr"]
             full = keep.numel() == p["n"]
             if events is None:
-                zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
-                zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws)
+                zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws, w_layout=p["layout"])
+                zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws,
+                                      w_layout=p["layout"])
             else:
                 # one event pair per product; a call that first extracts kept columns
                 # into the scratch buffer (HBM-bound copy kernels) is charged only the
@@ -132,8 +138,8 @@ def main() -> int:
                     if ws is not None and not full:
                         if pr.mode == zr.DROP_K and op in ("fwd", "dW"):
                             srcs = [p["X"]]
-                        elif pr.mode == zr.DROP_N:
-                            srcs = {"fwd": [p["W"]], "dX": [p["dY"], p["W"]], "dW": [p["dY"]]}[op]
+                        elif pr.mode == zr.DROP_N and op in ("dX", "dW"):
+                            srcs = [p["dY"]]
                     x0, x1, e0, e1 = ev(), ev(), ev(), ev()
                     if srcs:
                         x0.record()
@@ -145,11 +151,13 @@ def main() -> int:
                         x1.record()
                     e0.record()
                     if op == "fwd":
-                        zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws)
+                        zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws, w_layout=p["layout"])
                     elif op == "dX":
-                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], need_dW=False, workspace=ws)
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], need_dW=False,
+                                              workspace=ws, w_layout=p["layout"])
                     else:
-                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False, workspace=ws)
+                        zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False,
+                                              workspace=ws, w_layout=p["layout"])
                     e1.record()
                     events.append((zr.debug_last_kernel(), fl, e0, e1, (x0, x1, len(srcs)) if srcs else None))
 
@@ -273,12 +281,14 @@ def main() -> int:
     for p in projs:
         W = p["W"]
         Wprev = W.clone()
-        wsb = torch.empty(max(16, zr.priority_workspace_bytes(W.shape[0], W.shape[1], p["pr"].mode)),
+        # in both storage layouts the pruned axis is the row axis of the stored matrix
+        wsb = torch.empty(max(16, zr.priority_workspace_bytes(W.shape[0], W.shape[1], zr.DROP_K)),
                           dtype=torch.uint8, device=dev)
         out = torch.empty(p["n"], dtype=torch.float32, device=dev)
-        ms = timed(lambda: zr.priority_scores(W, Wprev, p["pr"].mode, scores=out, workspace=wsb))
+        assert W.shape[0] == p["n"]
+        ms = timed(lambda: zr.priority_scores(W, Wprev, zr.DROP_K, scores=out, workspace=wsb))
         nbytes = 2.0 * W.numel() * W.element_size()
-        pri[p["pr"].name] = {"shape": list(W.shape), "mode": "DROP_N" if p["pr"].mode == zr.DROP_N else "DROP_K",
+        pri[p["pr"].name] = {"stored_shape": list(W.shape), "scores": "one per stored row",
                              "us": ms * 1e3, "GB/s": nbytes / (ms * 1e-3) / 1e9,
                              "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del Wprev, wsb
@@ -317,7 +327,8 @@ def main() -> int:
                                + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
                                + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
                    "path": "resize_select_multi (one launch for the 5 projections) + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
-                           "with the optional scratch buffer for the extracted kept columns of activations and weights"},
+                           "with the optional scratch buffer for the extracted kept columns of activations; column-parallel shards "
+                           "stored [N x K], row-parallel [K x N] (the kept list selects rows of the stored weight, no weight copy)"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "extract": extract, "by_ratio": sweep, "aux": aux,

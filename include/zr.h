@@ -66,6 +66,17 @@ typedef enum { ZR_F32 = 0, ZR_BF16 = 1 } zr_dtype;
  *             shards): Y and dW lose columns -> imputed; dX keeps its shape. */
 typedef enum { ZR_DROP_N = 0, ZR_DROP_K = 1 } zr_mode;
 
+/* How the weight shard (and its gradient) is stored.
+ *  ZR_W_KN: W[K x N] row-major ([in, out]); ldw >= N.
+ *  ZR_W_NK: the transpose, [N x K] row-major ([out, in], the layout of the
+ *           paper's weight matrix, Sec. 3.1); ldw >= K.
+ * The mathematics is the same; the layout decides whether the kept list selects
+ * ROWS of the stored matrix (contiguous: gathered while the tiles are loaded,
+ * the weight is never copied) or single elements of every row (slower loaders).
+ * Rows are selected for (ZR_W_KN, ZR_DROP_K) and (ZR_W_NK, ZR_DROP_N): store
+ * row-parallel shards as KN and column-parallel shards as NK. */
+typedef enum { ZR_W_KN = 0, ZR_W_NK = 1 } zr_w_layout;
+
 /* Imputation policies of Sec. 3.1 ("what value should be imputed"). */
 typedef enum {
     ZR_IMPUTE_ZERO = 0,     /* +0.0 (the paper's final choice) */
@@ -106,18 +117,14 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
 
 /* Size of the optional scratch buffer of the forward / backward calls below.
  * With a DEVICE buffer of at least this many bytes (16-byte aligned) the calls
- * first extract the kept columns of every operand they would otherwise gather
- * along its contiguous axis (Sec. 3.1: the remaining columns are concatenated)
- * into it, [rows x n_keep rounded up to 64] bf16, zero padded, and then run the
- * products on ordinary loads:
- *   DROP_K: X[:,S] [M x w]                       (forward, dW)
- *   DROP_N: dY[:,S] [M x w] (dX, dW), then W[:,S] [K x w] (forward at offset 0; dX
- *           behind the extracted dY)
- * Rows of W (DROP_K) are contiguous and are never copied.  A buffer that holds
- * only the first part is used for that part.  Without it (NULL, or too small)
- * every gather is done in flight by the GEMM loaders; results are the same to
- * the last bit either way.  Returns 0 when no call would use a workspace
- * (fp32).  Pure host function. */
+ * first extract the kept columns of the ACTIVATION they would otherwise gather
+ * along its contiguous axis (X[:,S] for DROP_K, dY[:,S] for DROP_N; Sec. 3.1:
+ * the remaining columns of the input are concatenated) into it,
+ * [M x n_keep rounded up to 64] bf16, zero padded, and then run the products on
+ * ordinary loads.  The weight shard is never copied or compacted, in either
+ * layout.  Without it (NULL, or too small) every gather is done in flight by
+ * the GEMM loaders; results are the same to the last bit either way.  Returns 0
+ * when no call would use a workspace (fp32).  Pure host function. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
 /* The extraction step on its own (Sec. 3.1: the remaining columns of the input
@@ -133,8 +140,8 @@ int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
 /* Forward of the resized linear layer (Sec. 3.1, forward paragraph).
  *  DROP_K: Y = X[:,S] W[S,:]            (full shape, nothing to impute)
  *  DROP_N: Y[:,S] = X W[:,S];  Y[:,P] imputed by `policy`
- *  X [M x K] ldx, W [K x N] ldw, Y [M x N] ldy (out, every element written).
- *  keep_idx[n_keep] indexes K (DROP_K) or N (DROP_N).
+ *  X [M x K] ldx, W stored per w_layout with ldw, Y [M x N] ldy (out, every
+ *  element written).  keep_idx[n_keep] indexes K (DROP_K) or N (DROP_N).
  *  prev_Y: previous iteration's Y [M x N] with leading dimension ldy, needed for
  *  ZR_IMPUTE_SAME in DROP_N only (may alias Y: dropped positions then stay as
  *  they are); ignored otherwise.
@@ -142,28 +149,29 @@ int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
  *  contents are undefined afterwards; calls that share one must be ordered on
  *  one stream.
  *  Launches: 1 for ZERO and SAME (both written by the product's own epilogue),
- *  +1 with a workspace, +1 for AVERAGE.
- *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE, POLICY, LIMIT, HIP. */
+ *  +1 with a workspace in DROP_K, +1 for AVERAGE.
+ *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE (also a bad w_layout), POLICY, LIMIT, HIP. */
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy, const void* prev_Y,
+                          int mode, int w_layout, int dtype, int policy, const void* prev_Y,
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of the resized linear layer (Sec. 3.1, backward paragraph; the
  * upstream gradient is never pruned in the paper's DROP_K case).
  *  DROP_K: dX[:,S] = dY W[S,:]^T, dX[:,P] imputed;  dW[S,:] = X[:,S]^T dY, dW[P,:] imputed
  *  DROP_N: dX = dY[:,S] W[:,S]^T (full shape);      dW[:,S] = X^T dY[:,S], dW[:,P] imputed
- *  dX [M x K] lddx and dW [K x N] lddw are outputs; either may be NULL to skip
- *  that product.  prev_dX / prev_dW (same shapes and leading dimensions as dX /
- *  dW) are read for ZR_IMPUTE_SAME only.  workspace: as for the forward call.
+ *  dX [M x K] lddx and dW (stored like W: [K x N] or [N x K], lddw) are outputs;
+ *  either may be NULL to skip that product.  prev_dX / prev_dW (same shapes,
+ *  layout and leading dimensions as dX / dW) are read for ZR_IMPUTE_SAME only.
+ *  workspace: as for the forward call.
  *  Errors as for the forward call. */
 int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           const void* dY, int64_t lddy,
                           void* dX, int64_t lddx, void* dW, int64_t lddw,
                           int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy,
+                          int mode, int w_layout, int dtype, int policy,
                           const void* prev_dX, const void* prev_dW,
                           void* workspace, size_t workspace_bytes, void* stream);
 
@@ -182,7 +190,8 @@ int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
 
 /* Weight-variation scores (Sec. 3.2 "Priority Pruning"; Algorithm 1):
  *   scores[i] = mean over the slice's elements of |W_t - W_prev|, for every index
- *   i of the pruned axis of W[K x N] (columns for ZR_DROP_N, rows for ZR_DROP_K);
+ *   i of the pruned axis of W[K x N] (columns for ZR_DROP_N, rows for ZR_DROP_K;
+ *   a shard stored [N x K] is passed as that [N x K] matrix with the other mode);
  * incremental update (Sec. 3.2): when prev_keep_idx is given, an index that is
  * NOT in it (it was pruned in the previous epoch) receives prev_scores[i] instead.
  *  W_t, W_prev [K x N] with a common leading dimension ld; scores fp32 [n] out;

@@ -67,11 +67,9 @@ extern "C" {
 
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype)
 {
-    (void)N;
-    if (dtype != ZR_BF16 || M < 1 || K < 1 || n_keep < 1) return 0;
-    // extracted activation columns [M x width], then (DROP_N) extracted weight columns [K x width]
-    const size_t width = (size_t)round_up64(n_keep);
-    return (size_t)M * width * 2 + (mode == ZR_DROP_N ? (size_t)K * width * 2 : 0);
+    (void)K; (void)N; (void)mode;
+    if (dtype != ZR_BF16 || M < 1 || n_keep < 1) return 0;
+    return (size_t)M * (size_t)round_up64(n_keep) * 2;      // extracted activation columns [M x width]
 }
 
 const char* zr_status_string(int status)
@@ -151,16 +149,38 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
     return launch_select_multi(m, count, (hipStream_t)stream);
 }
 
+// The weight operand B(j,c) of the three products for both storage layouts of the
+// shard: KN = W[K x N] row-major, NK = W^T stored as [N x K] row-major (the
+// [out, in] layout).  Whichever axis the kept list indexes, one of the layouts
+// makes it the ROW axis of the stored matrix, so that the list only selects
+// contiguous rows and the weight is neither gathered element-wise nor copied.
+static Operand weight_fwd(const void* W, int64_t ldw, int K, int N, int mode, int layout, const int32_t* S)
+{
+    // forward: B(j,c) = W[c,j], c over K (DROP_K: c -> S[c]; DROP_N: j -> S[j])
+    if (layout == ZR_W_KN)
+        return mode == ZR_DROP_K ? operand(W, ldw, false, S, nullptr, K, N) : operand(W, ldw, false, nullptr, S, K, N);
+    return mode == ZR_DROP_K ? operand(W, ldw, true, nullptr, S, N, K) : operand(W, ldw, true, S, nullptr, N, K);
+}
+
+static Operand weight_dx(const void* W, int64_t ldw, int K, int N, int mode, int layout, const int32_t* S)
+{
+    // dX: B(j,c) = W[j,c], j over K, c over N (DROP_K: j -> S[j]; DROP_N: c -> S[c])
+    if (layout == ZR_W_KN)
+        return mode == ZR_DROP_K ? operand(W, ldw, true, S, nullptr, K, N) : operand(W, ldw, true, nullptr, S, K, N);
+    return mode == ZR_DROP_K ? operand(W, ldw, false, nullptr, S, N, K) : operand(W, ldw, false, S, nullptr, N, K);
+}
+
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy, const void* prev_Y,
+                          int mode, int w_layout, int dtype, int policy, const void* prev_Y,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!X || !W || !Y) return ZR_ERR_NULL;
     int st = check_common(M, K, N, keep_idx, n_keep, mode, dtype, policy);
     if (st != ZR_OK) return st;
-    if (ldx < K || ldw < N || ldy < N) return ZR_ERR_SHAPE;
+    if (w_layout != ZR_W_KN && w_layout != ZR_W_NK) return ZR_ERR_MODE;
+    if (ldx < K || ldw < (w_layout == ZR_W_KN ? N : K) || ldy < N) return ZR_ERR_SHAPE;
     const bool full = n_keep == (mode == ZR_DROP_N ? N : K);   // ascending + unique + full count = identity
     const bool needs_prev = mode == ZR_DROP_N && policy == ZR_IMPUTE_SAME && !full;
     if (needs_prev && !prev_Y) return ZR_ERR_POLICY;
@@ -170,6 +190,7 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     GemmDesc d;
     d.dtype = dtype;
     d.out = Y; d.ldo = ldy; d.keep_idx = S; d.I = M;
+    d.B = weight_fwd(W, ldw, K, N, mode, w_layout, S);
     if (mode == ZR_DROP_K) {
         // Y[m,j] = sum_{c<n'} X[m,S[c]] * W[S[c],j]
         const Extract ex = plan_extract(X, ldx, M, K, n_keep, dtype, workspace, workspace_bytes);
@@ -181,20 +202,11 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
         } else {
             d.A = operand(X, ldx, true, nullptr, S, M, K);
         }
-        d.B = operand(W, ldw, false, S, nullptr, K, N);
         d.J = N; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = N;
         return launch_gemm(d, s);
     }
     // Y[m,S[j]] = sum_k X[m,k] * W[k,S[j]], dropped columns imputed
     d.A = operand(X, ldx, true, nullptr, nullptr, M, K);
-    const Extract ew = plan_extract(W, ldw, K, N, n_keep, dtype, workspace, workspace_bytes);
-    if (ew.use) {
-        st = launch_compact_cols(W, ldw, K, N, keep_idx, n_keep, workspace, ew.width, ew.width, s);
-        if (st != ZR_OK) return st;
-        d.B = operand(workspace, ew.width, false, nullptr, nullptr, K, ew.width);
-    } else {
-        d.B = operand(W, ldw, false, nullptr, S, K, N);
-    }
     d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
     if (needs_prev) d.prev = prev_Y;            // Same: copied by the scatter epilogue itself
     st = launch_gemm(d, s);
@@ -207,7 +219,7 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           void* dX, int64_t lddx, void* dW, int64_t lddw,
                           int32_t M, int32_t K, int32_t N,
                           const int32_t* keep_idx, int32_t n_keep,
-                          int mode, int dtype, int policy,
+                          int mode, int w_layout, int dtype, int policy,
                           const void* prev_dX, const void* prev_dW,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -215,9 +227,11 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     if ((dX && !W) || (dW && !X)) return ZR_ERR_NULL;
     int st = check_common(M, K, N, keep_idx, n_keep, mode, dtype, policy);
     if (st != ZR_OK) return st;
+    if (w_layout != ZR_W_KN && w_layout != ZR_W_NK) return ZR_ERR_MODE;
+    const bool kn = w_layout == ZR_W_KN;
     if (lddy < N) return ZR_ERR_SHAPE;
-    if (dX && (ldw < N || lddx < K)) return ZR_ERR_SHAPE;
-    if (dW && (ldx < K || lddw < N)) return ZR_ERR_SHAPE;
+    if (dX && (ldw < (kn ? N : K) || lddx < K)) return ZR_ERR_SHAPE;
+    if (dW && (ldx < K || lddw < (kn ? N : K))) return ZR_ERR_SHAPE;
     const bool full = n_keep == (mode == ZR_DROP_N ? N : K);
     if (policy == ZR_IMPUTE_SAME && !full) {
         if (dW && !prev_dW) return ZR_ERR_POLICY;
@@ -244,10 +258,10 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     d.keep_idx = S;
     if (dX) {
         d.out = dX; d.ldo = lddx; d.I = M;
+        d.B = weight_dx(W, ldw, K, N, mode, w_layout, S);
         if (mode == ZR_DROP_K) {
             // dX[m,S[j]] = sum_n dY[m,n] * W[S[j],n], dropped columns imputed
             d.A = operand(dY, lddy, true, nullptr, nullptr, M, N);
-            d.B = operand(W, ldw, true, S, nullptr, K, N);
             d.J = n_keep; d.C = N; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = K;
             if (same) d.prev = prev_dX;
         } else {
@@ -258,20 +272,6 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             } else {
                 d.A = operand(dY, lddy, true, nullptr, S, M, N);
             }
-            // W[:,S] goes behind the extracted dY[:,S] when the scratch buffer holds both
-            Extract ew{false, 0};
-            if (ex.use) {
-                const size_t used = (size_t)M * (size_t)ex.width * 2;
-                ew = plan_extract(W, ldw, K, N, n_keep, dtype, (char*)workspace + used, workspace_bytes - used);
-                if (ew.use) {
-                    st = launch_compact_cols(W, ldw, K, N, keep_idx, n_keep, (char*)workspace + used, ew.width,
-                                             ew.width, s);
-                    if (st != ZR_OK) return st;
-                    d.B = operand((char*)workspace + used, ew.width, true, nullptr, nullptr, K, ew.width);
-                    d.B.zero_padded = true;
-                }
-            }
-            if (!ew.use) d.B = operand(W, ldw, true, nullptr, S, K, N);
             d.J = K; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = K;
         }
         st = launch_gemm(d, s);
@@ -282,25 +282,29 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
         }
     }
     if (dW) {
+        // dW has the layout of W.  KN: D[i=k, j=n]; NK: D[i=n, j=k]; contraction over the tokens.
         d.out = dW; d.ldo = lddw; d.C = M;
         d.prev = same ? prev_dW : nullptr;
-        if (mode == ZR_DROP_K) {
-            // dW[S[i],n] = sum_m X[m,S[i]] * dY[m,n], dropped rows imputed
-            if (ex.use) d.A = operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width);
-            else d.A = operand(X, ldx, false, nullptr, S, M, K);
-            d.B = operand(dY, lddy, false, nullptr, nullptr, M, N);
-            d.I = n_keep; d.J = N; d.epilogue = full ? EPI_PLAIN : EPI_ROW_SCATTER; d.out_full = K;
-        } else {
-            // dW[k,S[j]] = sum_m X[m,k] * dY[m,S[j]], dropped columns imputed
-            d.A = operand(X, ldx, false, nullptr, nullptr, M, K);
-            if (ex.use) d.B = operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width);
-            else d.B = operand(dY, lddy, false, nullptr, S, M, N);
-            d.I = K; d.J = n_keep; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
-        }
+        const Operand xs = (mode == ZR_DROP_K)
+            ? (ex.use ? operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width)
+                      : operand(X, ldx, false, nullptr, S, M, K))
+            : operand(X, ldx, false, nullptr, nullptr, M, K);
+        const Operand dys = (mode == ZR_DROP_N)
+            ? (ex.use ? operand(workspace, ex.width, false, nullptr, nullptr, M, ex.width)
+                      : operand(dY, lddy, false, nullptr, S, M, N))
+            : operand(dY, lddy, false, nullptr, nullptr, M, N);
+        const int ik = mode == ZR_DROP_K ? n_keep : K;       // extent of the K index of D
+        const int in = mode == ZR_DROP_N ? n_keep : N;       // extent of the N index of D
+        // the kept list indexes rows of the stored dW in (KN, DROP_K) and (NK, DROP_N), columns otherwise
+        const bool rows_pruned = kn == (mode == ZR_DROP_K);
+        if (kn) { d.A = xs; d.B = dys; d.I = ik; d.J = in; }
+        else    { d.A = dys; d.B = xs; d.I = in; d.J = ik; }
+        d.epilogue = full ? EPI_PLAIN : (rows_pruned ? EPI_ROW_SCATTER : EPI_COL_SCATTER);
+        d.out_full = mode == ZR_DROP_K ? K : N;
         st = launch_gemm(d, s);
         if (st != ZR_OK) return st;
         if (post) {
-            st = launch_impute(dW, lddw, K, N, mode == ZR_DROP_K ? 0 : 1, keep_idx, n_keep, policy,
+            st = launch_impute(dW, lddw, kn ? K : N, kn ? N : K, rows_pruned ? 0 : 1, keep_idx, n_keep, policy,
                                prev_dW, dtype, s);
             if (st != ZR_OK) return st;
         }

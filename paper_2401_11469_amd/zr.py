@@ -14,6 +14,7 @@ from typing import Optional, Tuple
 import torch
 
 DROP_N, DROP_K = 0, 1
+W_KN, W_NK = 0, 1
 ZERO, AVERAGE, SAME = 0, 1, 2
 F32, BF16 = 0, 1
 
@@ -35,12 +36,12 @@ _lib.zr_resize_select.restype = ctypes.c_int
 _lib.zr_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int, ctypes.c_int]
 _lib.zr_workspace_bytes.restype = ctypes.c_size_t
 _lib.zr_resized_linear_fwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32,
-                                       _vp, _i32, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp,
+                                       _vp, _i32, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp,
                                        _vp, ctypes.c_size_t, _vp]
 _lib.zr_resized_linear_fwd.restype = ctypes.c_int
 _lib.zr_resized_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                        _i32, _i32, _i32, _vp, _i32,
-                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
                                        _vp, ctypes.c_size_t, _vp]
 _lib.zr_resized_linear_bwd.restype = ctypes.c_int
 _lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, ctypes.c_int, _vp]
@@ -182,11 +183,12 @@ def resize_select_multi(scores, ratios, keep_idx=None, drop_idx=None, stream=Non
 def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor, mode: int,
                        policy: int = ZERO, prev_Y: Optional[torch.Tensor] = None,
                        Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                       stream=None) -> torch.Tensor:
+                       stream=None, w_layout: int = W_KN) -> torch.Tensor:
+    """W is [K, N] (w_layout=W_KN) or [N, K] (W_NK)."""
     M, K = X.shape
-    N = W.shape[1]
-    if W.shape[0] != K or W.dtype != X.dtype:
-        raise ValueError("W must be [K, N] with X's dtype")
+    N = W.shape[1] if w_layout == W_KN else W.shape[0]
+    if tuple(W.shape) != ((K, N) if w_layout == W_KN else (N, K)) or W.dtype != X.dtype:
+        raise ValueError("W must be [K, N] (W_KN) or [N, K] (W_NK) with X's dtype")
     if Y is None:
         Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
     (xp, ldx), (wp, ldw), (yp, ldy) = _mat(X, "X"), _mat(W, "W"), _mat(Y, "Y")
@@ -194,7 +196,7 @@ def resized_linear_fwd(X: torch.Tensor, W: torch.Tensor, keep_idx: torch.Tensor,
     if prev_Y is not None and ldp != ldy:
         raise ValueError("prev_Y must share Y's leading dimension")
     _check(_lib.zr_resized_linear_fwd(xp, ldx, wp, ldw, yp, ldy, M, K, N,
-                                      keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
+                                      keep_idx.data_ptr(), keep_idx.numel(), mode, w_layout, _dtype_code(X),
                                       policy, pp, *_ws(workspace), _stream(stream)))
     return Y
 
@@ -203,22 +205,25 @@ def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_
                        mode: int, policy: int = ZERO, prev_dX: Optional[torch.Tensor] = None,
                        prev_dW: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
                        dW: Optional[torch.Tensor] = None, need_dX: bool = True, need_dW: bool = True,
-                       workspace: Optional[torch.Tensor] = None, stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+                       workspace: Optional[torch.Tensor] = None, stream=None,
+                       w_layout: int = W_KN) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """W and dW are [K, N] (w_layout=W_KN) or [N, K] (W_NK)."""
     M, K = X.shape
-    N = W.shape[1]
-    if dY.shape != (M, N):
-        raise ValueError("dY must be [M, N]")
+    N = dY.shape[1]
+    wshape = (K, N) if w_layout == W_KN else (N, K)
+    if dY.shape[0] != M or tuple(W.shape) != wshape:
+        raise ValueError("dY must be [M, N] and W [K, N] (W_KN) or [N, K] (W_NK)")
     if need_dX and dX is None:
         dX = torch.empty((M, K), dtype=X.dtype, device=X.device)
     if need_dW and dW is None:
-        dW = torch.empty((K, N), dtype=X.dtype, device=X.device)
+        dW = torch.empty(wshape, dtype=X.dtype, device=X.device)
     (xp, ldx), (wp, ldw), (gp, ldg) = _mat(X, "X"), _mat(W, "W"), _mat(dY, "dY")
     (dxp, lddx), (dwp, lddw) = _mat(dX if need_dX else None, "dX"), _mat(dW if need_dW else None, "dW")
     (pxp, ldpx), (pwp, ldpw) = _mat(prev_dX, "prev_dX"), _mat(prev_dW, "prev_dW")
     if (prev_dX is not None and need_dX and ldpx != lddx) or (prev_dW is not None and need_dW and ldpw != lddw):
         raise ValueError("previous tensors must share the outputs' leading dimensions")
     _check(_lib.zr_resized_linear_bwd(xp, ldx, wp, ldw, gp, ldg, dxp, lddx, dwp, lddw, M, K, N,
-                                      keep_idx.data_ptr(), keep_idx.numel(), mode, _dtype_code(X),
+                                      keep_idx.data_ptr(), keep_idx.numel(), mode, w_layout, _dtype_code(X),
                                       policy, pxp, pwp, *_ws(workspace), _stream(stream)))
     return (dX if need_dX else None), (dW if need_dW else None)
 

@@ -55,7 +55,7 @@ def test_workspace_bytes_host_function(lib):
     f = lib.zr_workspace_bytes
     f.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_int, ctypes.c_int]
     f.restype = ctypes.c_size_t
-    assert f(8192, 4096, 3072, 2304, 0, 1) == (8192 + 4096) * 2304 * 2   # DROP_N: dY[:,S] and W[:,S]; 2304 = 36 * 64
+    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2            # dY[:,S]; 2304 = 36 * 64 (the weight is never copied)
     assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2            # DROP_K: X[:,S] only; 2064 -> 2112
     assert f(8192, 4096, 3072, 2304, 0, 0) == 0                        # fp32: no workspace path
     assert f(0, 8, 8, 4, 0, 1) == 0
@@ -102,18 +102,21 @@ def test_argument_validation_returns_before_any_gpu_work(lib):
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     fwd = lib.zr_resized_linear_fwd
     fwd.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
-                    ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
     fwd.restype = ctypes.c_int
     p = 0x1000  # never dereferenced: every call below fails validation first
-    assert fwd(None, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, 0, None) == 1      # NULL
-    assert fwd(p, 8, p, 8, p, 8, 0, 8, 8, p, 4, 0, 1, 0, None, None, 0, None) == 2          # M < 1
-    assert fwd(p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, 0, None) == 2          # ldx < K
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 9, 0, 1, 0, None, None, 0, None) == 4          # n_keep > n
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 0, 0, 1, 0, None, None, 0, None) == 4          # n_keep < 1
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 7, 0, None, None, 0, None) == 5          # dtype
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 5, 1, 0, None, None, 0, None) == 6          # mode
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 9, None, None, 0, None) == 7          # policy
-    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 2, None, None, 0, None) == 7          # SAME without prev
+    assert fwd(None, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, 0, None) == 1      # NULL
+    assert fwd(p, 8, p, 8, p, 8, 0, 8, 8, p, 4, 0, 0, 1, 0, None, None, 0, None) == 2          # M < 1
+    assert fwd(p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, 0, None) == 2          # ldx < K
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 9, 0, 0, 1, 0, None, None, 0, None) == 4          # n_keep > n
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 0, 0, 0, 1, 0, None, None, 0, None) == 4          # n_keep < 1
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 7, 0, None, None, 0, None) == 5          # dtype
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 5, 0, 1, 0, None, None, 0, None) == 6          # mode
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 9, None, None, 0, None) == 7          # policy
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 2, None, None, 0, None) == 7          # SAME without prev
+    assert fwd(p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 0, 3, 1, 0, None, None, 0, None) == 6          # w_layout
+    assert fwd(p, 8, p, 8, p, 16, 4, 8, 16, p, 4, 0, 0, 1, 0, None, None, 0, None) == 2        # KN: ldw < N
+    assert fwd(p, 16, p, 8, p, 8, 4, 16, 8, p, 4, 0, 1, 1, 0, None, None, 0, None) == 2        # NK: ldw < K
     sel = lib.zr_resize_select
     sel.argtypes = [vp, i32, i32, ctypes.c_double, vp, vp, i64, vp]
     sel.restype = ctypes.c_int
@@ -141,8 +144,8 @@ def test_argument_validation_returns_before_any_gpu_work(lib):
     assert ext(p, 7, 4, 7, p, 4, p, 64, 1, None) == 2          # odd row length
     bwd = lib.zr_resized_linear_bwd
     bwd.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
-                    ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
     bwd.restype = ctypes.c_int
-    assert bwd(p, 8, p, 8, p, 8, None, 8, None, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, None, 0, None) == 1
-    assert bwd(p, 8, p, 8, p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 1, 0, None, None, None, 0, None) == 2
-    assert bwd(p, 8, p, 8, p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 1, 1, 2, None, None, None, 0, None) == 7
+    assert bwd(p, 8, p, 8, p, 8, None, 8, None, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, None) == 1
+    assert bwd(p, 8, p, 8, p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, None) == 2
+    assert bwd(p, 8, p, 8, p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 1, 0, 1, 2, None, None, None, 0, None) == 7

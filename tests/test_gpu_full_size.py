@@ -46,6 +46,11 @@ def _check_projection(zr, oracle, cid, pi, ratio):
     mode, n = pr.mode, pr.n_axis
 
     X, W, dY = (torch.from_numpy(a).to(tdt).cuda() for a in (Xh, Wh, dYh))
+    # as bench.py stores the shards: column-parallel (DROP_N) ones [N x K], so that the
+    # kept list selects rows of the stored weight in both modes
+    nk = mode == DROP_N
+    layout = 1 if nk else 0
+    Wdev = W.t().contiguous() if nk else W
     keep, drop = zr.resize_select(torch.from_numpy(scores).cuda(), r)
     S, P = oracle.resize_select(scores, r)
     assert np.array_equal(keep.cpu().numpy(), S) and np.array_equal(drop.cpu().numpy(), P)   # bit-exact
@@ -53,12 +58,14 @@ def _check_projection(zr, oracle, cid, pi, ratio):
 
     Y = torch.full((M, N), 3.0, dtype=tdt, device="cuda")
     dX = torch.full((M, K), 3.0, dtype=tdt, device="cuda")
-    dW = torch.full((K, N), 3.0, dtype=tdt, device="cuda")
+    dW = torch.full((N, K) if nk else (K, N), 3.0, dtype=tdt, device="cuda")
     # as bench.py launches it: with the optional scratch buffer
     ws = torch.empty(max(16, zr.workspace_bytes(M, K, N, len(S), mode, tdt)), dtype=torch.uint8, device="cuda")
-    zr.resized_linear_fwd(X, W, keep, mode, Y=Y, workspace=ws)
-    zr.resized_linear_bwd(X, W, dY, keep, mode, dX=dX, dW=dW, workspace=ws)
+    zr.resized_linear_fwd(X, Wdev, keep, mode, Y=Y, workspace=ws, w_layout=layout)
+    zr.resized_linear_bwd(X, Wdev, dY, keep, mode, dX=dX, dW=dW, workspace=ws, w_layout=layout)
     torch.cuda.synchronize()
+    if nk:
+        dW = dW.t()          # a [K x N] view for the checks below
 
     # (1) whole tensors: masked-dense identity with a library GEMM in fp32
     mask = torch.zeros(n, dtype=torch.float32, device="cuda")

@@ -308,7 +308,10 @@ def test_select_multi_matches_single_vector_calls(zr, torch_mod, oracle):
 
 # ------------------------------------------------------------------- GEMMs ---
 
-def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False):
+W_KN, W_NK = 0, 1
+
+
+def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False, w_layout=W_KN):
     """fwd + bwd through the C ABI; returns float64 numpy (Y, dX, dW).
     use_ws: hand the calls the optional scratch buffer (extracted-activation path)."""
     M, K = case["X"].shape
@@ -318,23 +321,27 @@ def run_layer(zr, torch, case, S, mode, dtype, policy=ZERO, pad=0, use_ws=False)
         nbytes = zr.workspace_bytes(M, K, N, len(S), mode, _tdtype(torch, dtype))
         ws = torch.full((max(nbytes, 16),), 0x7F, dtype=torch.uint8, device="cuda")   # NaN-pattern garbage
     ld = (lambda c: c + pad) if pad else (lambda c: None)
+    # the weight, its gradient and the gradient's previous value live in the chosen layout
+    nk = w_layout == W_NK
+    wl_ = (lambda a: np.ascontiguousarray(a.T)) if nk else (lambda a: a)
+    wcols = K if nk else N
     X = to_gpu(torch, case["X"], dtype, ld(K))
-    W = to_gpu(torch, case["W"], dtype, ld(N))
+    W = to_gpu(torch, wl_(case["W"]), dtype, ld(wcols))
     dY = to_gpu(torch, case["dY"], dtype, ld(N))
     keep = idx_gpu(torch, S)
     pY = to_gpu(torch, case["prev_Y"], dtype, ld(N)) if policy == SAME else None
     pdX = to_gpu(torch, case["prev_dX"], dtype, ld(K)) if policy == SAME else None
-    pdW = to_gpu(torch, case["prev_dW"], dtype, ld(N)) if policy == SAME else None
+    pdW = to_gpu(torch, wl_(case["prev_dW"]), dtype, ld(wcols)) if policy == SAME else None
     Y = to_gpu(torch, np.full((M, N), 555.0, np.float32), dtype, ld(N))
     dX = to_gpu(torch, np.full((M, K), 555.0, np.float32), dtype, ld(K))
-    dW = to_gpu(torch, np.full((K, N), 555.0, np.float32), dtype, ld(N))
-    zr.resized_linear_fwd(X, W, keep, mode, policy, pY, Y=Y, workspace=ws)
-    zr.resized_linear_bwd(X, W, dY, keep, mode, policy, pdX, pdW, dX=dX, dW=dW, workspace=ws)
+    dW = to_gpu(torch, wl_(np.full((K, N), 555.0, np.float32)), dtype, ld(wcols))
+    zr.resized_linear_fwd(X, W, keep, mode, policy, pY, Y=Y, workspace=ws, w_layout=w_layout)
+    zr.resized_linear_bwd(X, W, dY, keep, mode, policy, pdX, pdW, dX=dX, dW=dW, workspace=ws, w_layout=w_layout)
     torch.cuda.synchronize()
     if pad:
         for t in (Y, dX, dW):
             assert torch.all(t._base[:, t.shape[1]:] == 777.0), "padding overwritten"
-    return to_np(Y), to_np(dX), to_np(dW)
+    return to_np(Y), to_np(dX), (to_np(dW).T if nk else to_np(dW))
 
 
 def check_layer(oracle, case, S, mode, dtype, policy, got, tol=None):
@@ -408,6 +415,29 @@ def test_layer_parity_other_policies(zr, torch_mod, oracle, dtype, mode, policy)
     S = subset(9, n, (3 * n) // 5)
     got = run_layer(zr, torch, case, S, mode, dtype, policy)
     check_layer(oracle, case, S, mode, dtype, policy, got)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("policy", [ZERO, AVERAGE, SAME])
+@pytest.mark.parametrize("M,K,N,pad,use_ws", [(140, 264, 200, 0, False), (300, 520, 392, 0, True),
+                                              (130, 77, 51, 3, False), (257, 512, 320, 8, True)])
+def test_layer_parity_weight_stored_out_by_in(zr, torch_mod, oracle, dtype, mode, policy, M, K, N, pad, use_ws):
+    """The shard, its gradient and the gradient's previous value stored [N x K]:
+    same mathematics, the kept list now selects rows of the stored weight in DROP_N."""
+    torch = torch_mod
+    case = wl.random_case(1000 + M + K + N, M, K, N, dtype)
+    n = N if mode == DROP_N else K
+    for n_keep in sorted({1, (3 * n) // 5, n - 1, n}):
+        S = subset(n_keep + 3, n, n_keep)
+        got = run_layer(zr, torch, case, S, mode, dtype, policy, pad=pad, use_ws=use_ws and dtype == "bf16",
+                        w_layout=W_NK)
+        check_layer(oracle, case, S, mode, dtype, policy, got)
+        if dtype == "bf16" and policy == ZERO and not pad:
+            # both layouts contract in the same order: bitwise equal results
+            ref = run_layer(zr, torch, case, S, mode, dtype, policy, w_layout=W_KN)
+            for x, y in zip(got, ref):
+                assert np.array_equal(x, y)
 
 
 def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
