@@ -31,12 +31,12 @@ HBM_PEAK_GBS = 8000.0
 # reads for --calibrate-copy; the summary under profiles/ gives the commands.
 # Counters cannot be read from inside the timed run, so the figures live here.
 PMC_TRAFFIC_BYTES = {
-    "fast_kernel<DmaQ, DmaQ, 256, 256, 2, 4>": 349132586,
-    "fast_kernel<DmaQ, DmaQ, 128, 128, 2, 2>": 288678397,
-    "fast_kernel<DmaP, LdQG, 256, 256, 2, 4>": 306249536,
-    "fast_kernel<DmaP, LdPG, 256, 256, 2, 4>": 324240213,
-    "fast_kernel<DmaP, DmaQ, 256, 256, 2, 4>": 219878583,
-    "fast_kernel<DmaP, DmaP, 256, 256, 2, 4>": 279298933,
+    "fast_kernel<DmaP, DmaQ, 256, 256, 2, 4>": 255392218,
+    "fast_kernel<DmaQ, DmaQ, 192, 256, 2, 4>": 398145856,
+    "fast_kernel<DmaP, DmaP, 256, 256, 2, 4>": 259746416,
+    "fast_kernel<DmaQ, DmaQ, 128, 128, 2, 2>": 298625089,
+    "fast_kernel<DmaP, DmaP, 128, 128, 2, 2>": 132539420,
+    "fast_kernel<DmaP, DmaP, 256, 192, 4, 2>": 210923386,
 }
 
 
@@ -113,6 +113,8 @@ def main() -> int:
         return sum(wl.kept_flops(M, p["pr"].K, p["pr"].N, p["n"],
                                  zr.keep_count(p["n"], wl.ratio_for(cfg, p["pr"], ratio))) for p in projs)
 
+    extracts = []
+
     def run_step(ratio: float, events=None):
         # the step's selections: one launch for all projections of the shard
         keeps, _ = zr.resize_select_multi([p["scores"] for p in projs],
@@ -126,30 +128,15 @@ def main() -> int:
                 zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws,
                                       w_layout=p["layout"])
             else:
-                # one event pair per product; a call that first extracts kept columns
-                # into the scratch buffer (HBM-bound copy kernels) is charged only the
-                # GEMM: the same extractions are timed on their own right before and
-                # subtracted
+                # one event pair per product, recorded by the library right around the
+                # product's own GEMM launch(es) (zr_debug_time_next_product), so that an
+                # extraction into the scratch buffer is not charged to the GEMM; the
+                # extraction kernel is bracketed separately where it runs on its own
                 fl = 2.0 * M * pr.K * pr.N * keep.numel() / p["n"]
-                ev = lambda: torch.cuda.Event(enable_timing=True)
-                width = (keep.numel() + 63) // 64 * 64
                 for op in ("fwd", "dX", "dW"):
-                    srcs = []
-                    if ws is not None and not full:
-                        if pr.mode == zr.DROP_K and op in ("fwd", "dW"):
-                            srcs = [p["X"]]
-                        elif pr.mode == zr.DROP_N and op in ("dX", "dW"):
-                            srcs = [p["dY"]]
-                    x0, x1, e0, e1 = ev(), ev(), ev(), ev()
-                    if srcs:
-                        x0.record()
-                        off = 0
-                        for src in srcs:
-                            rows = src.shape[0]
-                            zr.extract_kept_columns(src, keep, out=ws[off:off + rows * width * 2].view(tdt).view(rows, width))
-                            off += rows * width * 2
-                        x1.record()
-                    e0.record()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(); e1.record()            # creates the HIP events
+                    zr.debug_time_next_product(e0, e1)
                     if op == "fwd":
                         zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws, w_layout=p["layout"])
                     elif op == "dX":
@@ -158,8 +145,15 @@ def main() -> int:
                     else:
                         zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False,
                                               workspace=ws, w_layout=p["layout"])
-                    e1.record()
-                    events.append((zr.debug_last_kernel(), fl, e0, e1, (x0, x1, len(srcs)) if srcs else None))
+                    events.append((zr.debug_last_kernel(), fl, e0, e1))
+                if ws is not None and not full:
+                    src = p["X"] if pr.mode == zr.DROP_K else p["dY"]
+                    width = (keep.numel() + 63) // 64 * 64
+                    x0, x1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    x0.record()
+                    zr.extract_kept_columns(src, keep, out=ws[:M * width * 2].view(tdt).view(M, width))
+                    x1.record()
+                    extracts.append((x0, x1))
 
     ratios = wl.ratio_sequence(args.config, args.warmup + args.steps)
 
@@ -187,19 +181,13 @@ def main() -> int:
         run_step(r, events)
     torch.cuda.synchronize()
     per = {}
-    extract_ms = 0.0
-    n_extract = 0
-    for label, fl, e0, e1, xe in events:
+    for label, fl, e0, e1 in events:
         d = per.setdefault(label, [0, 0.0, 0.0])
-        ms = e0.elapsed_time(e1)
-        if xe is not None:
-            x = xe[0].elapsed_time(xe[1])
-            extract_ms += x
-            n_extract += xe[2]
-            ms = max(ms - x, 0.0)
         d[0] += 1
         d[1] += fl
-        d[2] += ms
+        d[2] += e0.elapsed_time(e1)
+    extract_ms = sum(a.elapsed_time(b) for a, b in extracts)
+    n_extract = len(extracts)
     kernels = {k: {"launches": v[0], "avg_ms": v[2] / v[0], "tflops": v[1] / (v[2] * 1e-3) / 1e12}
                for k, v in per.items()}
     dom = max(per.items(), key=lambda kv: kv[1][2])

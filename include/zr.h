@@ -253,6 +253,14 @@ int zr_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t n,
  * process launched.  Not thread safe. */
 const char* zr_debug_last_kernel(void);
 
+/* Profiling aid: the NEXT forward / backward / accumulate product of this process
+ * records the two caller-owned HIP events (hipEvent_t, created with timing) on
+ * its stream immediately before and after its own GEMM launch(es), leaving out an
+ * extraction that precedes it and an imputation pass that follows.  One shot; a
+ * backward call that computes dX and dW times the first of the two.  Not thread
+ * safe.  Errors: NULL. */
+int zr_debug_time_next_product(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -91,6 +91,14 @@ const char* zr_status_string(int status)
 
 const char* zr_debug_last_kernel(void) { return g_last_kernel; }
 
+int zr_debug_time_next_product(void* start_event, void* stop_event)
+{
+    if (!start_event || !stop_event) return ZR_ERR_NULL;
+    g_time_start = (hipEvent_t)start_event;
+    g_time_stop = (hipEvent_t)stop_event;
+    return ZR_OK;
+}
+
 int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
                             const int32_t* keep_idx, int32_t n_keep,
                             void* out, int64_t ldo, int dtype, void* stream)

@@ -72,6 +72,7 @@ struct GemmDesc {
 };
 
 extern char g_last_kernel[128];
+extern hipEvent_t g_time_start, g_time_stop;   // see launch_gemm
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
 int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,

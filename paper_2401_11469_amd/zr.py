@@ -68,6 +68,8 @@ _lib.zr_migrated_accumulate.restype = ctypes.c_int
 _lib.zr_resize_select_multi.argtypes = [_i32, ctypes.POINTER(_vp), ctypes.POINTER(_i32), ctypes.POINTER(_f64),
                                         ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]
 _lib.zr_resize_select_multi.restype = ctypes.c_int
+_lib.zr_debug_time_next_product.argtypes = [_vp, _vp]
+_lib.zr_debug_time_next_product.restype = ctypes.c_int
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -309,6 +311,13 @@ def migrated_accumulate(out: torch.Tensor, A: torch.Tensor, B: torch.Tensor, b_t
     _check(_lib.zr_migrated_accumulate(ap, lda, bp, ldb, 1 if b_transposed else 0, op, ldo, M, N, C,
                                        _dtype_code(out), _stream(stream)))
     return out
+
+
+def debug_time_next_product(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> None:
+    """The next product records the two events right around its GEMM launch(es).
+    The events must have been created with enable_timing=True and recorded once
+    before (torch creates the HIP event lazily)."""
+    _check(_lib.zr_debug_time_next_product(start.cuda_event, stop.cuda_event))
 
 
 def debug_last_kernel() -> str:

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
             "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes",
             "zr_extract_kept_columns", "zr_debug_last_kernel", "zr_priority_scores", "zr_pruning_ratio",
             "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes", "zr_migration_range",
-            "zr_migrated_accumulate", "zr_resize_select_multi"} <= set(names)
+            "zr_migrated_accumulate", "zr_resize_select_multi", "zr_debug_time_next_product"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
