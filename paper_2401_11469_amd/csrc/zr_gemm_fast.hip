@@ -526,12 +526,19 @@ struct DmaP {
 
 // Contraction axis strided in memory (optional row list on it): LDS keeps the
 // memory rows as they are (row c = R consecutive columns), with the 16-byte
-// chunk index XORed by 2 * (c & 3); fragments are read with the transposing
+// chunk index XORed by ZR_QSWZ * (c & 3); fragments are read with the transposing
 // ds_read_tr16_b64, which hands a lane 4 consecutive c of ONE column out of a
-// 4 (c) x 16 (columns) block read by its 16-lane group.
+// 4 (c) x 16 (columns) block read by its 16-lane group.  Two such groups (32
+// lanes, 4 rows x 64 bytes) are served together; the rows are a multiple of
+// 256 bytes apart, so the XOR has to move each of the 4 rows to its own
+// 64-byte quarter of the 64 banks: factor 4 (a factor of 2 leaves rows 0/1 and
+// 2/3 on the same banks; the conflict counter showed exactly that, 1 in 2).
 // A tile width R that is not a power of two (192) keeps the LDS geometry of the
-// next power of two RP: the lanes of the chunks beyond R are switched off, their
-// LDS slots stay unwritten and are never read.
+// next power of two RP: the lanes whose chunk lies beyond R are switched off,
+// their LDS slots stay unwritten and are never read.
+#ifndef ZR_QSWZ
+#define ZR_QSWZ 4
+#endif
 template <int R, int NT>
 struct DmaQ {
     static constexpr const char* NAME = "DmaQ";
@@ -558,7 +565,7 @@ struct DmaQ {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int col = w0 + t * 32 + 16 * ((lane >> 4) & 1) + 4 * (t16 & 3);
-                coloff[t] = (((col >> 3) ^ (2 * (t16 >> 2))) << 2) + ((col & 7) >> 1);
+                coloff[t] = (((col >> 3) ^ (ZR_QSWZ * (t16 >> 2))) << 2) + ((col & 7) >> 1);
             }
         }
         __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
@@ -585,11 +592,14 @@ struct DmaQ {
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
-        // the swizzle below only permutes chunks inside aligned groups of 8
-        active_ = ((tid & 63) % CPR) * 8 < R;
+        // a lane's LDS slot is fixed; the XOR decides which chunk of the row it fetches.
+        // tile_row(q) & 3 does not depend on q (instructions of one wavefront are a
+        // multiple of 4 rows apart), so neither does the lane being inside the tile
+        static_assert((RPI * NW) % 4 == 0, "rows of successive instructions must agree modulo 4");
+        active_ = (((tid & 63) % CPR) ^ (ZR_QSWZ * (tile_row(0, tid) & 3))) * 8 < R;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            const int chunk = ((tid & 63) % CPR) ^ (2 * (tile_row(q, tid) & 3));
+            const int chunk = ((tid & 63) % CPR) ^ (ZR_QSWZ * (tile_row(q, tid) & 3));
             colp[q] = op.base + min(r0 + chunk * 8, op.n_c - 8);     // the readable row length is a multiple of 8
         }
         rows_for(op, 0, C, tid);
