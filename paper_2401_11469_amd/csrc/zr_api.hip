@@ -61,15 +61,56 @@ Extract plan_extract(const void* src, int64_t ld, int32_t M, int32_t n, int32_t 
     return e;
 }
 
+// Average imputation through the product's own epilogue: the tail of the caller's
+// scratch buffer holds the per-tile sums, ceil(extent / 128) slots of `len` floats
+// (extent = kept count along the summed axis, len = length of the other axis).
+size_t avg_bytes(int len, int n_keep) { return ((size_t)((n_keep + 127) / 128) * (size_t)len * 4 + 15) & ~(size_t)15; }
+
+// Splits the workspace: returns the sums' address (nullptr: no room, the stand-alone
+// second pass is used) and shrinks `bytes` to what is left for the extraction.
+float* carve_avg(void* workspace, size_t& bytes, size_t need)
+{
+    if (!workspace || need == 0 || bytes < need + 16) return nullptr;
+    const size_t off = (bytes - need) & ~(size_t)15;
+    if ((uintptr_t)workspace % 16 != 0) return nullptr;
+    bytes = off;
+    return (float*)((char*)workspace + off);
+}
+
+// One product with Average imputation: zero the sums, multiply (the scatter epilogue
+// writes results, +0 and the sums), then mean and fill; or, without room for the
+// sums, multiply and run the stand-alone pass that re-reads the kept slices.
+int gemm_with_average(GemmDesc& d, float* sums, void* out, int64_t ld, int rows, int cols, int axis,
+                      const int32_t* keep_idx, int n_keep, int dtype, hipStream_t s)
+{
+    int st;
+    if (sums) {
+        const int len = axis == 1 ? rows : cols;
+        const int slots = (n_keep + 127) / 128;
+        st = launch_zero_f32(sums, (size_t)slots * (size_t)len, s);
+        if (st != ZR_OK) return st;
+        d.avg_partial = sums; d.avg_len = len;
+        st = launch_gemm(d, s);
+        d.avg_partial = nullptr;
+        if (st != ZR_OK) return st;
+        return launch_mean_fill(out, ld, rows, cols, axis, keep_idx, n_keep, sums, slots, dtype, s);
+    }
+    st = launch_gemm(d, s);
+    if (st != ZR_OK) return st;
+    return launch_impute(out, ld, rows, cols, axis, keep_idx, n_keep, ZR_IMPUTE_AVERAGE, nullptr, dtype, s);
+}
+
 }  // namespace
 
 extern "C" {
 
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype)
 {
-    (void)K; (void)N; (void)mode;
-    if (dtype != ZR_BF16 || M < 1 || n_keep < 1) return 0;
-    return (size_t)M * (size_t)round_up64(n_keep) * 2;      // extracted activation columns [M x width]
+    (void)mode;
+    if (M < 1 || K < 1 || N < 1 || n_keep < 1) return 0;
+    // extracted activation columns [M x width] (bf16 only), then the per-tile sums of Average imputation
+    const size_t act = dtype == ZR_BF16 ? (size_t)M * (size_t)round_up64(n_keep) * 2 : 0;
+    return act + avg_bytes(std::max(M, std::max(K, N)), n_keep) + 16;
 }
 
 const char* zr_status_string(int status)
@@ -194,6 +235,8 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     if (needs_prev && !prev_Y) return ZR_ERR_POLICY;
     hipStream_t s = (hipStream_t)stream;
     const int32_t* S = full ? nullptr : keep_idx;
+    const bool average = mode == ZR_DROP_N && policy == ZR_IMPUTE_AVERAGE && !full;
+    float* sums = average ? carve_avg(workspace, workspace_bytes, avg_bytes(M, n_keep)) : nullptr;
 
     GemmDesc d;
     d.dtype = dtype;
@@ -217,9 +260,8 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     d.A = operand(X, ldx, true, nullptr, nullptr, M, K);
     d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
     if (needs_prev) d.prev = prev_Y;            // Same: copied by the scatter epilogue itself
-    st = launch_gemm(d, s);
-    if (st != ZR_OK || full || policy != ZR_IMPUTE_AVERAGE) return st;
-    return launch_impute(Y, ldy, M, N, 1, keep_idx, n_keep, policy, prev_Y, dtype, s);
+    if (average) return gemm_with_average(d, sums, Y, ldy, M, N, 1, keep_idx, n_keep, dtype, s);
+    return launch_gemm(d, s);
 }
 
 int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
@@ -248,7 +290,14 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     hipStream_t s = (hipStream_t)stream;
     const int32_t* S = full ? nullptr : keep_idx;
     const bool same = !full && policy == ZR_IMPUTE_SAME;       // fused into the scatter epilogues
-    const bool post = !full && policy == ZR_IMPUTE_AVERAGE;    // second pass over the output
+    const bool post = !full && policy == ZR_IMPUTE_AVERAGE;    // sums in the epilogue, then mean and fill
+    float* sums = nullptr;
+    if (post) {
+        size_t need = 0;
+        if (dX && mode == ZR_DROP_K) need = avg_bytes(M, n_keep);
+        if (dW) need = std::max(need, avg_bytes(mode == ZR_DROP_K ? N : K, n_keep));
+        sums = carve_avg(workspace, workspace_bytes, need);
+    }
 
     // one extraction serves both products: X[:,S] (DROP_K, used by dW) or dY[:,S] (DROP_N)
     Extract ex{false, 0};
@@ -282,12 +331,9 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             }
             d.J = K; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = K;
         }
-        st = launch_gemm(d, s);
+        if (post && mode == ZR_DROP_K) st = gemm_with_average(d, sums, dX, lddx, M, K, 1, keep_idx, n_keep, dtype, s);
+        else st = launch_gemm(d, s);
         if (st != ZR_OK) return st;
-        if (post && mode == ZR_DROP_K) {
-            st = launch_impute(dX, lddx, M, K, 1, keep_idx, n_keep, policy, prev_dX, dtype, s);
-            if (st != ZR_OK) return st;
-        }
     }
     if (dW) {
         // dW has the layout of W.  KN: D[i=k, j=n]; NK: D[i=n, j=k]; contraction over the tokens.
@@ -309,13 +355,10 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
         else    { d.A = dys; d.B = xs; d.I = in; d.J = ik; }
         d.epilogue = full ? EPI_PLAIN : (rows_pruned ? EPI_ROW_SCATTER : EPI_COL_SCATTER);
         d.out_full = mode == ZR_DROP_K ? K : N;
-        st = launch_gemm(d, s);
+        if (post) st = gemm_with_average(d, sums, dW, lddw, kn ? K : N, kn ? N : K, rows_pruned ? 0 : 1, keep_idx,
+                                         n_keep, dtype, s);
+        else st = launch_gemm(d, s);
         if (st != ZR_OK) return st;
-        if (post) {
-            st = launch_impute(dW, lddw, kn ? K : N, kn ? N : K, rows_pruned ? 0 : 1, keep_idx, n_keep, policy,
-                               prev_dW, dtype, s);
-            if (st != ZR_OK) return st;
-        }
     }
     return ZR_OK;
 }

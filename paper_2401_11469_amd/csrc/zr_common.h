@@ -69,6 +69,13 @@ struct GemmDesc {
     const void* prev = nullptr;
     // out = round(out + D) in fp32 (plain epilogue only): the local reduce of migrated work
     bool accumulate = false;
+    // Average imputation, first phase (scatter epilogues only): every tile adds up the
+    // results it stores, per output row over its columns (column scatter) or per output
+    // column over its rows (row scatter), and writes the sums to
+    // avg_partial[slot * avg_len + index], slot = the tile's position along the summed
+    // axis.  The buffer holds ceil(extent / 128) slots and must be zero beforehand.
+    float* avg_partial = nullptr;
+    int avg_len = 0;
 };
 
 extern char g_last_kernel[128];
@@ -89,6 +96,11 @@ int launch_select_multi(const SelectMulti& m, int count, hipStream_t stream);
 int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
                   const int32_t* keep_idx, int n_keep, int policy, const void* prev,
                   int dtype, hipStream_t stream);
+// Average imputation, second phase: mean[i] = (sum over slots of partial[slot*len + i]) / n_keep
+// (in slot order, left in slot 0), then the dropped columns / rows receive the mean.
+int launch_zero_f32(float* p, size_t count, hipStream_t stream);
+int launch_mean_fill(void* out, int64_t ld, int rows, int cols, int axis, const int32_t* keep_idx, int n_keep,
+                     float* partial, int slots, int dtype, hipStream_t stream);
 int launch_compact_cols(const void* in, int64_t ld, int rows, int n, const int32_t* keep, int n_keep,
                         void* out, int64_t ldo, int width, hipStream_t stream);
 int launch_priority_scores(const void* Wt, const void* Wp, int64_t ld, int K, int N, int mode,

@@ -81,6 +81,8 @@ struct KArgs {
     int tiles_j;
     const void* prev;       // Same imputation source (layout of out) or nullptr
     int accumulate;         // add the old contents of out (plain epilogue)
+    float* avg_partial;     // Average imputation: per-tile sums of the stored results, or nullptr
+    int avg_len;            // entries per slot of avg_partial
 };
 
 // ---------------------------------------------------------------------------
@@ -513,6 +515,15 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
         // width for the last tile); kept ones receive results, the rest +0
         for (int q = tid; q < cols_valid; q += NT) sidx[q] = clamp_idx(g.keep[j0 + q], g.out_full);
         __syncthreads();
+        if (g.avg_partial) {
+            // sum of this tile's stored (rounded) results per output row, in column order
+            float* dst = g.avg_partial + (size_t)tj * (size_t)g.avg_len + i0;
+            for (int row = tid; row < rows_valid; row += NT) {
+                float sum = 0.f;
+                for (int c = 0; c < cols_valid; ++c) sum += Ty<DT>::to_f32(Cs[row * CP + c]);
+                dst[row] = sum;
+            }
+        }
         const int start = j0 == 0 ? 0 : sidx[0];
         const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(g.keep[j0 + BN], g.out_full);
         for (int chunk = start; chunk < end; chunk += NT) {
@@ -521,10 +532,25 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
                 const int jj = lower_bound_lds(sidx, cols_valid, p);
                 const bool hit = jj < cols_valid && sidx[jj] == p;
                 E* o = out + (size_t)i0 * (size_t)g.ldo + p;
-                const E* pv = prev ? prev + (size_t)i0 * (size_t)g.ldo + p : nullptr;
-                for (int row = 0; row < rows_valid; ++row) {
-                    o[(size_t)row * (size_t)g.ldo] =
-                        hit ? Cs[row * CP + jj] : (pv ? pv[(size_t)row * (size_t)g.ldo] : E(0));
+                if (hit || !prev) {
+                    for (int row = 0; row < rows_valid; ++row)
+                        o[(size_t)row * (size_t)g.ldo] = hit ? Cs[row * CP + jj] : E(0);
+                } else {
+                    // Same: a position is read and written by this thread only (also when the
+                    // previous tensor is the output itself), so loads go out in batches
+                    const E* pv = prev + (size_t)i0 * (size_t)g.ldo + p;
+                    constexpr int RB = 16;
+                    for (int row = 0; row < rows_valid; row += RB) {
+                        E old[RB];
+#pragma unroll
+                        for (int u = 0; u < RB; ++u)
+                            old[u] = row + u < rows_valid ? pv[(size_t)(row + u) * (size_t)g.ldo] : E(0);
+#pragma unroll
+                        for (int u = 0; u < RB; ++u) {
+                            if (row + u >= rows_valid) break;
+                            o[(size_t)(row + u) * (size_t)g.ldo] = old[u];
+                        }
+                    }
                 }
             }
         }
@@ -536,6 +562,15 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
         for (int q = tid; q < rows_valid; q += NT) sidx[q] = clamp_idx(g.keep[i0 + q], g.out_full);
     }
     __syncthreads();
+    if (scatter_rows && g.avg_partial) {
+        // sum of this tile's stored (rounded) results per output column, in row order
+        float* dst = g.avg_partial + (size_t)ti * (size_t)g.avg_len + j0;
+        for (int col = tid; col < cols_valid; col += NT) {
+            float sum = 0.f;
+            for (int r = 0; r < rows_valid; ++r) sum += Ty<DT>::to_f32(Cs[r * CP + col]);
+            dst[col] = sum;
+        }
+    }
     constexpr int CPR = BN / VEC;               // 16-byte chunks per tile row
     for (int q = tid; q < BM * CPR; q += NT) {
         const int row = q / CPR;
@@ -614,6 +649,7 @@ int launch_dt(const GemmDesc& d, hipStream_t stream)
     k.out_vec = ((uintptr_t)d.out % 16 == 0) && (d.ldo % VEC == 0);
     k.tiles_j = 0;
     k.prev = d.prev; k.accumulate = d.accumulate ? 1 : 0;
+    k.avg_partial = d.epilogue == EPI_PLAIN ? nullptr : d.avg_partial; k.avg_len = d.avg_len;
     const bool av = vec_ok(d.A), bv = vec_ok(d.B);
     if (d.A.c_contig && !d.B.c_contig) return launch_fmt<DT, true, false>(k, av, bv, stream);
     if (d.A.c_contig && d.B.c_contig) return launch_fmt<DT, true, true>(k, av, bv, stream);

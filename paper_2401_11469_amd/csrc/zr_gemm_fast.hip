@@ -105,6 +105,9 @@ struct FArgs {
     int out_full;
     const E* prev;          // Same imputation source (layout of out) or nullptr
     int accumulate;         // add the old contents of out (plain epilogue)
+    float* avg_partial;     // Average imputation: per-tile sums of the stored results, or nullptr
+    int avg_len;            // entries per slot of avg_partial
+    int avg_slot_base;      // slot of this launch's first tile along the summed axis
     // sub-rectangle of D this launch covers, in elements (multiples of 256 except at
     // the far edges of D) and its tile grid
     int i_base, j_base, i_end, j_end;
@@ -821,6 +824,15 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         // the last one).  Thread <-> one aligned pair of original columns.
         for (int q = tid; q < cols_valid; q += NT) idxB[q] = clamp_idx(g.keep[j0 + q], g.out_full);
         __syncthreads();
+        if (g.avg_partial) {
+            // sum of this tile's stored (rounded) results per output row, in column order
+            float* dst = g.avg_partial + (size_t)(g.avg_slot_base + tj) * (size_t)g.avg_len + i0;
+            for (int row = tid; row < rows_valid; row += NT) {
+                float sum = 0.f;
+                for (int c = 0; c < cols_valid; ++c) sum += bf16_bits_to_f32(Cs[row * CP + c]);
+                dst[row] = sum;
+            }
+        }
         const int start = j0 == 0 ? 0 : idxB[0];
         const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(g.keep[j0 + BN], g.out_full);
         for (int pbase = (start & ~1) + 2 * tid; pbase < end; pbase += 2 * NT) {
@@ -850,22 +862,43 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 }
                 continue;
             }
-            // Same: dropped positions copy the previous tensor's value
+            // Same: dropped positions copy the previous tensor's value.  The previous tensor
+            // may be the output itself, but a position is only ever read and written by this
+            // thread, so the loads of a batch of rows may all go out before its stores
+            // (one load latency per batch instead of one per row).
             const E* pv = g.prev + (size_t)i0 * (size_t)g.ldo + p0;
+            constexpr int RB = 16;
             if (own0 && own1) {
                 const bool need_prev = !(k0 && k1);
-                for (int row = 0; row < rows_valid; ++row) {
-                    const uint32_t old = need_prev ? *(const uint32_t*)(pv + (size_t)row * (size_t)g.ldo) : 0u;
-                    const uint32_t v0 = k0 ? Cs[row * CP + r0] : (old & 0xffffu);
-                    const uint32_t v1 = k1 ? Cs[row * CP + r1] : (old >> 16);
-                    *(uint32_t*)(o + (size_t)row * (size_t)g.ldo) = v0 | (v1 << 16);
+                for (int row = 0; row < rows_valid; row += RB) {
+                    uint32_t old[RB];
+#pragma unroll
+                    for (int u = 0; u < RB; ++u)
+                        old[u] = (need_prev && row + u < rows_valid)
+                                     ? *(const uint32_t*)(pv + (size_t)(row + u) * (size_t)g.ldo) : 0u;
+#pragma unroll
+                    for (int u = 0; u < RB; ++u) {
+                        if (row + u >= rows_valid) break;
+                        const uint32_t v0 = k0 ? Cs[(row + u) * CP + r0] : (old[u] & 0xffffu);
+                        const uint32_t v1 = k1 ? Cs[(row + u) * CP + r1] : (old[u] >> 16);
+                        *(uint32_t*)(o + (size_t)(row + u) * (size_t)g.ldo) = v0 | (v1 << 16);
+                    }
                 }
-            } else if (own0) {
-                for (int row = 0; row < rows_valid; ++row)
-                    o[(size_t)row * (size_t)g.ldo] = k0 ? Cs[row * CP + r0] : pv[(size_t)row * (size_t)g.ldo];
-            } else if (own1) {
-                for (int row = 0; row < rows_valid; ++row)
-                    o[(size_t)row * (size_t)g.ldo + 1] = k1 ? Cs[row * CP + r1] : pv[(size_t)row * (size_t)g.ldo + 1];
+            } else if (own0 || own1) {
+                const int side = own0 ? 0 : 1;
+                const bool kept = own0 ? k0 : k1;
+                const int rr = own0 ? r0 : r1;
+                for (int row = 0; row < rows_valid; row += RB) {
+                    E old[RB];
+#pragma unroll
+                    for (int u = 0; u < RB; ++u)
+                        old[u] = (!kept && row + u < rows_valid) ? pv[(size_t)(row + u) * (size_t)g.ldo + side] : E(0);
+#pragma unroll
+                    for (int u = 0; u < RB; ++u) {
+                        if (row + u >= rows_valid) break;
+                        o[(size_t)(row + u) * (size_t)g.ldo + side] = kept ? Cs[(row + u) * CP + rr] : old[u];
+                    }
+                }
             }
         }
         return;
@@ -875,6 +908,15 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     if (scatter_rows)
         for (int q = tid; q < rows_valid; q += NT) idxA[q] = clamp_idx(g.keep[i0 + q], g.out_full);
     __syncthreads();
+    if (scatter_rows && g.avg_partial) {
+        // sum of this tile's stored (rounded) results per output column, in row order
+        float* dst = g.avg_partial + (size_t)(g.avg_slot_base + ti) * (size_t)g.avg_len + j0;
+        for (int col = tid; col < cols_valid; col += NT) {
+            float sum = 0.f;
+            for (int r = 0; r < rows_valid; ++r) sum += bf16_bits_to_f32(Cs[r * CP + col]);
+            dst[col] = sum;
+        }
+    }
     constexpr int CPR = BN / 8;
     for (int q = tid; q < BM * CPR; q += NT) {
         const int row = q / CPR;
@@ -904,7 +946,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 // Host side
 // ---------------------------------------------------------------------------
 template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
-int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream)
+int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream, int slot_base = 0)
 {
     if (i_end <= i_base || j_end <= j_base) return ZR_OK;
     constexpr int smem = fast_smem_bytes<LA<BM, 64 * WM * WN>::WORDS, LB<BN, 64 * WM * WN>::WORDS, BM, BN>();
@@ -919,6 +961,7 @@ int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
              LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
     FArgs k = a;
     k.i_base = i_base; k.i_end = i_end; k.j_base = j_base; k.j_end = j_end;
+    k.avg_slot_base = slot_base;
     k.tiles_i = (i_end - i_base + BM - 1) / BM;
     k.tiles_j = (j_end - j_base + BN - 1) / BN;
     const int64_t tiles = (int64_t)k.tiles_i * k.tiles_j;
@@ -1003,8 +1046,14 @@ int launch_shape(const FArgs& a, hipStream_t stream)
     if (st != ZR_OK || (sc.big_i_end >= a.I && sc.big_j_end >= a.J)) return st;
     char big[128];
     snprintf(big, sizeof(big), "%s", g_last_kernel);
-    if (sc.cut_rows) st = launch_tile<LA, LB, 128, 128, 2, 2>(a, sc.big_i_end, a.I, 0, a.J, stream);
-    else st = launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, sc.big_j_end, a.J, stream);
+    // Average sums: the remainder panel's tiles continue the slot numbering of the big
+    // panel along the summed axis when the cut runs across that axis; panels that
+    // cover different output rows (columns) never meet in a slot
+    const bool sums_over_j = a.epilogue == EPI_COL_SCATTER;
+    if (sc.cut_rows) st = launch_tile<LA, LB, 128, 128, 2, 2>(a, sc.big_i_end, a.I, 0, a.J, stream,
+                                                              sums_over_j ? 0 : sc.big_i_end / 256);
+    else st = launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, sc.big_j_end, a.J, stream,
+                                                  sums_over_j ? sc.big_j_end / 256 : 0);
     snprintf(g_last_kernel, sizeof(g_last_kernel), "%.60s + 128x128 remainder panel", big);
     return st;
 }
@@ -1038,6 +1087,7 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     a.I = d.I; a.J = d.J; a.C = d.C;
     a.out = (E*)d.out; a.ldo = d.ldo; a.epilogue = d.epilogue; a.keep = d.keep_idx; a.out_full = d.out_full;
     a.prev = (const E*)d.prev; a.accumulate = d.accumulate ? 1 : 0;
+    a.avg_partial = d.epilogue == EPI_PLAIN ? nullptr : d.avg_partial; a.avg_len = d.avg_len; a.avg_slot_base = 0;
     a.tiles_i = a.tiles_j = 0;
     a.i_base = a.j_base = a.i_end = a.j_end = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;

@@ -110,6 +110,66 @@ __global__ __launch_bounds__(256) void average_rows_kernel(
     }
 }
 
+// ---- Average from the per-tile sums of the product's epilogue ----------------
+__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// mean over the kept slices, slots added in slot order; left in slot 0
+__global__ __launch_bounds__(256) void mean_finish_kernel(float* __restrict__ partial, int slots, int len, int n_keep)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= len) return;
+    float sum = 0.f;
+    for (int s = 0; s < slots; ++s) sum += partial[(size_t)s * (size_t)len + i];
+    partial[i] = sum / (float)n_keep;
+}
+
+// axis 1: dropped column p of row r receives mean[r]
+template <typename T>
+__global__ __launch_bounds__(256) void mean_fill_cols_kernel(
+    T* __restrict__ out, int64_t ld, int rows, int cols, const int32_t* __restrict__ keep, int n_keep,
+    const float* __restrict__ mean)
+{
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= cols) return;
+    if (is_kept(keep, n_keep, p)) return;
+    const int r0 = blockIdx.y * FILL_ROWS;
+    const int r1 = min(rows, r0 + FILL_ROWS);
+    for (int r = r0; r < r1; ++r) Elem<T>::store(out + (size_t)r * (size_t)ld + (size_t)p, mean[r]);
+}
+
+// axis 0: dropped row r receives mean[c] in column c
+template <typename T>
+__global__ __launch_bounds__(256) void mean_fill_rows_kernel(
+    T* __restrict__ out, int64_t ld, int rows, int cols, const int32_t* __restrict__ keep, int n_keep,
+    const float* __restrict__ mean)
+{
+    const int r = blockIdx.x;
+    if (is_kept(keep, n_keep, r)) return;
+    T* o = out + (size_t)r * (size_t)ld;
+    for (int c = threadIdx.x; c < cols; c += 256) Elem<T>::store(o + c, mean[c]);
+}
+
+template <typename T>
+int mean_fill_typed(T* out, int64_t ld, int rows, int cols, int axis, const int32_t* keep, int n_keep,
+                    float* partial, int slots, hipStream_t stream)
+{
+    const int len = axis == 1 ? rows : cols;
+    hipLaunchKernelGGL(mean_finish_kernel, dim3((len + 255) / 256), dim3(256), 0, stream, partial, slots, len, n_keep);
+    if (axis == 1) {
+        dim3 grid((cols + 255) / 256, (rows + FILL_ROWS - 1) / FILL_ROWS);
+        hipLaunchKernelGGL(mean_fill_cols_kernel<T>, grid, dim3(256), 0, stream, out, ld, rows, cols, keep, n_keep,
+                           (const float*)partial);
+    } else {
+        hipLaunchKernelGGL(mean_fill_rows_kernel<T>, dim3(rows), dim3(256), 0, stream, out, ld, rows, cols, keep,
+                           n_keep, (const float*)partial);
+    }
+    return hip_status(hipGetLastError());
+}
+
 template <typename T>
 int impute_typed(T* out, int64_t ld, int rows, int cols, int axis, const int32_t* keep, int n_keep,
                  int policy, const T* prev, hipStream_t stream)
@@ -143,6 +203,21 @@ int impute_typed(T* out, int64_t ld, int rows, int cols, int axis, const int32_t
 }
 
 }  // namespace
+
+int launch_zero_f32(float* p, size_t count, hipStream_t stream)
+{
+    if (count == 0) return ZR_OK;
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, p, count);
+    return hip_status(hipGetLastError());
+}
+
+int launch_mean_fill(void* out, int64_t ld, int rows, int cols, int axis, const int32_t* keep_idx, int n_keep,
+                     float* partial, int slots, int dtype, hipStream_t stream)
+{
+    if (dtype == ZR_F32)
+        return mean_fill_typed<float>((float*)out, ld, rows, cols, axis, keep_idx, n_keep, partial, slots, stream);
+    return mean_fill_typed<uint16_t>((uint16_t*)out, ld, rows, cols, axis, keep_idx, n_keep, partial, slots, stream);
+}
 
 int launch_impute(void* out, int64_t ld, int rows, int cols, int axis,
                   const int32_t* keep_idx, int n_keep, int policy, const void* prev,

@@ -162,6 +162,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_multi_kernel(const SelectM
     select_body<STAGED>(m.scores[b], m.n[b], m.n_keep[b], m.keep[b], m.drop[b]);
 }
 
+__global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
+
 __global__ void validate_kernel(const int32_t* __restrict__ keep_idx, int n_keep, int n,
                                 int32_t* __restrict__ flag)
 {
@@ -200,7 +202,9 @@ int launch_select_multi(const SelectMulti& m, int count, hipStream_t stream)
 
 int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream)
 {
-    hipError_t e = hipMemsetAsync(flag, 0, sizeof(int32_t), stream);
+    // the flag is cleared by a kernel, not by a memset node
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return ZR_ERR_HIP;
     const int threads = 256;
     hipLaunchKernelGGL(validate_kernel, dim3((n_keep + threads - 1) / threads), dim3(threads), 0,

@@ -55,9 +55,11 @@ def test_workspace_bytes_host_function(lib):
     f = lib.zr_workspace_bytes
     f.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_int, ctypes.c_int]
     f.restype = ctypes.c_size_t
-    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2            # dY[:,S]; 2304 = 36 * 64 (the weight is never copied)
-    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2            # DROP_K: X[:,S] only; 2064 -> 2112
-    assert f(8192, 4096, 3072, 2304, 0, 0) == 0                        # fp32: no workspace path
+    def sums(length, n_keep):            # per-tile sums of Average imputation: ceil(n_keep/128) slots of fp32
+        return ((n_keep + 127) // 128 * length * 4 + 15) // 16 * 16 + 16
+    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2 + sums(8192, 2304)   # dY[:,S]; 2304 = 36 * 64
+    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2 + sums(8192, 2064)   # X[:,S]; 2064 -> 2112
+    assert f(256, 512, 256, 192, 0, 0) == sums(512, 192)                           # fp32: no extraction
     assert f(0, 8, 8, 4, 0, 1) == 0
 
 

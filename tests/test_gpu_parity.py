@@ -370,6 +370,17 @@ def check_layer(oracle, case, S, mode, dtype, policy, got, tol=None):
             assert np.array_equal(g, w)
             if policy == ZERO:
                 assert not np.any(np.signbit(g))
+    if P.size and policy == AVERAGE:
+        # imputed means, element by element: one rounding of the mean to the output type on
+        # top of the (averaged-out) roundings of the kept values it is taken over
+        Y, dX, dW = got
+        if mode == DROP_K:
+            pairs = [(dX[:, P], wantdX[:, P], wantdX), (dW[P, :], wantdW[P, :], wantdW)]
+        else:
+            pairs = [(Y[:, P], wantY[:, P], wantY), (dW[:, P], wantdW[:, P], wantdW)]
+        eps = 2.0 ** -8 if dtype == "bf16" else 1e-5
+        for g, w, whole in pairs:
+            assert np.max(np.abs(g - w)) <= eps * np.max(np.abs(whole))
     return wantY, wantdX, wantdW
 
 
@@ -430,14 +441,32 @@ def test_layer_parity_weight_stored_out_by_in(zr, torch_mod, oracle, dtype, mode
     n = N if mode == DROP_N else K
     for n_keep in sorted({1, (3 * n) // 5, n - 1, n}):
         S = subset(n_keep + 3, n, n_keep)
-        got = run_layer(zr, torch, case, S, mode, dtype, policy, pad=pad, use_ws=use_ws and dtype == "bf16",
-                        w_layout=W_NK)
+        got = run_layer(zr, torch, case, S, mode, dtype, policy, pad=pad, use_ws=use_ws, w_layout=W_NK)
         check_layer(oracle, case, S, mode, dtype, policy, got)
         if dtype == "bf16" and policy == ZERO and not pad:
             # both layouts contract in the same order: bitwise equal results
             ref = run_layer(zr, torch, case, S, mode, dtype, policy, w_layout=W_KN)
             for x, y in zip(got, ref):
                 assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (300, 520, 392), (700, 1100, 900)])
+def test_average_through_the_epilogue_sums(zr, torch_mod, oracle, dtype, mode, M, K, N):
+    """With scratch the Average policy takes its means from sums the product's tiles
+    write; without it from a second pass over the stored output.  Both follow the
+    oracle; shapes span one tile, several tiles, and the two-panel schedule."""
+    torch = torch_mod
+    case = wl.random_case(55 + M, M, K, N, dtype)
+    n = N if mode == DROP_N else K
+    for n_keep in sorted({1, n // 2, n - 1}):
+        S = subset(n_keep, n, n_keep)
+        for layout in (W_KN, W_NK):
+            a = run_layer(zr, torch, case, S, mode, dtype, AVERAGE, use_ws=True, w_layout=layout)
+            check_layer(oracle, case, S, mode, dtype, AVERAGE, a)
+        b = run_layer(zr, torch, case, S, mode, dtype, AVERAGE, use_ws=False)
+        check_layer(oracle, case, S, mode, dtype, AVERAGE, b)
 
 
 def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
