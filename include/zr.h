@@ -123,8 +123,12 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
  * [M x n_keep rounded up to 64] bf16, zero padded, and then run the products on
  * ordinary loads.  The weight shard is never copied or compacted, in either
  * layout.  Without it (NULL, or too small) every gather is done in flight by
- * the GEMM loaders; results are the same to the last bit either way.  Returns 0
- * when no call would use a workspace (fp32).  Pure host function. */
+ * the GEMM loaders; results are the same to the last bit either way.
+ * The tail of the buffer (both dtypes) serves ZR_IMPUTE_AVERAGE: the products'
+ * epilogues leave per-tile sums of the stored results there, from which the means
+ * of the dropped slices are taken; without it a second pass re-reads the kept
+ * slices (means equal up to fp32 summation order).  Pure host function;
+ * returns 0 on bad sizes. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
 /* The extraction step on its own (Sec. 3.1: the remaining columns of the input
@@ -149,7 +153,8 @@ int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
  *  contents are undefined afterwards; calls that share one must be ordered on
  *  one stream.
  *  Launches: 1 for ZERO and SAME (both written by the product's own epilogue),
- *  +1 with a workspace in DROP_K, +1 for AVERAGE.
+ *  +1 with a workspace in DROP_K; AVERAGE: +1 (stand-alone pass) or +3 small ones
+ *  (clear sums, means, fill) with a workspace.
  *  Errors: NULL, SHAPE, INDEX, DTYPE, MODE (also a bad w_layout), POLICY, LIMIT, HIP. */
 int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           void* Y, int64_t ldy, int32_t M, int32_t K, int32_t N,
