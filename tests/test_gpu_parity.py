@@ -562,3 +562,84 @@ def test_config1_full(zr, torch_mod, oracle):
     X, W, dY = (t[k].astype(np.float64) for k in ("X", "W", "dY"))
     for g, w in zip(got, (X @ W, dY @ W.T, X.T @ dY)):
         assert relf(g, w) <= 1e-5
+
+
+# ------------------------------------------------------ streams and graphs ---
+
+def _layer_step(zr, torch, t, ratio, ws):
+    """select + forward + backward of one shard into the buffers of `t` (current stream)."""
+    keeps, _ = zr.resize_select_multi([t["scores"]], [ratio], keep_idx=[t["keep"]], drop_idx=[t["drop"]])
+    keep = keeps[0]
+    zr.resized_linear_fwd(t["X"], t["W"], keep, t["mode"], Y=t["Y"], workspace=ws, w_layout=t["layout"])
+    zr.resized_linear_bwd(t["X"], t["W"], t["dY"], keep, t["mode"], dX=t["dX"], dW=t["dW"], workspace=ws,
+                          w_layout=t["layout"])
+
+
+def _shard(torch, zr, mode, M, K, N, seed):
+    case = wl.random_case(seed, M, K, N, "bf16")
+    n = N if mode == DROP_N else K
+    nk = mode == DROP_N
+    g = np.random.Generator(np.random.PCG64(seed))
+    t = dict(mode=mode, layout=W_NK if nk else W_KN, n=n, case=case,
+             X=to_gpu(torch, case["X"], "bf16"), dY=to_gpu(torch, case["dY"], "bf16"),
+             W=to_gpu(torch, np.ascontiguousarray(case["W"].T) if nk else case["W"], "bf16"),
+             scores=torch.from_numpy(g.random(n).astype(np.float32)).cuda(),
+             keep=torch.empty(n, dtype=torch.int32, device="cuda"), drop=torch.empty(n, dtype=torch.int32, device="cuda"),
+             Y=torch.empty((M, N), dtype=torch.bfloat16, device="cuda"),
+             dX=torch.empty((M, K), dtype=torch.bfloat16, device="cuda"),
+             dW=torch.empty((N, K) if nk else (K, N), dtype=torch.bfloat16, device="cuda"))
+    return t
+
+
+def _check_shard(oracle, t, ratio):
+    scores = t["scores"].cpu().numpy()
+    S, _ = oracle.resize_select(scores, ratio)
+    got = (to_np(t["Y"]), to_np(t["dX"]), to_np(t["dW"]).T if t["layout"] == W_NK else to_np(t["dW"]))
+    check_layer(oracle, t["case"], S, t["mode"], "bf16", ZERO, got)
+
+
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+def test_whole_path_on_a_side_stream(zr, torch_mod, oracle, mode):
+    """Every call takes the caller's stream; nothing runs on, or waits for, the default stream."""
+    torch = torch_mod
+    M, K, N = 300, 520, 392
+    t = _shard(torch, zr, mode, M, K, N, 2024)
+    ws = torch.empty(zr.workspace_bytes(M, K, N, t["n"], mode, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()                      # default priority
+    with torch.cuda.stream(side):
+        _layer_step(zr, torch, t, 0.3, ws)
+    side.synchronize()
+    _check_shard(oracle, t, 0.3)
+
+
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+def test_whole_path_in_a_captured_graph(zr, torch_mod, oracle, mode):
+    """No call allocates or synchronises, so select + forward + backward can be captured
+    once and replayed: the kept COUNT is fixed by the ratio, the kept SET follows the
+    scores present at replay time.  Every replay is checked, with eager work and
+    synchronisations between the replays."""
+    torch = torch_mod
+    M, K, N = 300, 520, 392
+    t = _shard(torch, zr, mode, M, K, N, 777)
+    ws = torch.empty(zr.workspace_bytes(M, K, N, t["n"], mode, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    ratio = 0.25
+    _layer_step(zr, torch, t, ratio, ws)            # warm-up: every kernel has run once
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        _layer_step(zr, torch, t, ratio, ws)
+    g = np.random.Generator(np.random.PCG64(5))
+    for rep in range(3):
+        t["scores"].copy_(torch.from_numpy(g.random(t["n"]).astype(np.float32)).cuda())   # new priorities
+        for buf in (t["Y"], t["dX"], t["dW"]):
+            buf.fill_(7.0)                                                               # eager work in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        _check_shard(oracle, t, ratio)
+        replayed = [x.clone() for x in (t["Y"], t["dX"], t["dW"], t["keep"])]
+        _layer_step(zr, torch, t, ratio, ws)                                             # the same step, eagerly
+        torch.cuda.synchronize()
+        for a, b in zip(replayed, (t["Y"], t["dX"], t["dW"], t["keep"])):
+            assert torch.equal(a, b)
