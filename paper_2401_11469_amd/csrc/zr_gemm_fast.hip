@@ -821,7 +821,10 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     if (g.epilogue == EPI_COL_SCATTER) {
         // The tile owns the original columns from its first kept column (0 for the
         // first tile) up to the next tile's first kept column (the full width for
-        // the last one).  Thread <-> one aligned pair of original columns.
+        // the last one).  Work item <-> one aligned pair of original columns over one
+        // of RG row groups, consecutive threads on consecutive pairs: a tile owns
+        // about BN / (1 - ratio) columns, i.e. fewer pairs than there are threads,
+        // and the row groups keep every thread busy with a short loop.
         for (int q = tid; q < cols_valid; q += NT) idxB[q] = clamp_idx(g.keep[j0 + q], g.out_full);
         __syncthreads();
         if (g.avg_partial) {
@@ -835,7 +838,14 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         }
         const int start = j0 == 0 ? 0 : idxB[0];
         const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(g.keep[j0 + BN], g.out_full);
-        for (int pbase = (start & ~1) + 2 * tid; pbase < end; pbase += 2 * NT) {
+        constexpr int RG = 8;
+        constexpr int ROWS_PER = (BM + RG - 1) / RG;
+        const int first = start & ~1;
+        const int npairs = (end - first + 1) >> 1;
+        for (int item = tid; item < npairs * RG; item += NT) {
+            const int rg = item / npairs;
+            const int pbase = first + 2 * (item - rg * npairs);
+            const int row_lo = rg * ROWS_PER, row_hi = min(rows_valid, row_lo + ROWS_PER);
             const int p0 = pbase, p1 = pbase + 1;
             const bool own0 = p0 >= start, own1 = p1 < end;
             int r0 = lower_bound_lds(idxB, cols_valid, p0);
@@ -848,16 +858,16 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             if (!g.prev) {
                 // dropped positions receive +0
                 if (own0 && own1) {
-                    for (int row = 0; row < rows_valid; ++row) {
+                    for (int row = row_lo; row < row_hi; ++row) {
                         const uint32_t v0 = k0 ? Cs[row * CP + r0] : 0u;
                         const uint32_t v1 = k1 ? Cs[row * CP + r1] : 0u;
                         *(uint32_t*)(o + (size_t)row * (size_t)g.ldo) = v0 | (v1 << 16);
                     }
                 } else if (own0) {
-                    for (int row = 0; row < rows_valid; ++row)
+                    for (int row = row_lo; row < row_hi; ++row)
                         o[(size_t)row * (size_t)g.ldo] = k0 ? Cs[row * CP + r0] : E(0);
                 } else if (own1) {
-                    for (int row = 0; row < rows_valid; ++row)
+                    for (int row = row_lo; row < row_hi; ++row)
                         o[(size_t)row * (size_t)g.ldo + 1] = k1 ? Cs[row * CP + r1] : E(0);
                 }
                 continue;
@@ -870,15 +880,15 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             constexpr int RB = 16;
             if (own0 && own1) {
                 const bool need_prev = !(k0 && k1);
-                for (int row = 0; row < rows_valid; row += RB) {
+                for (int row = row_lo; row < row_hi; row += RB) {
                     uint32_t old[RB];
 #pragma unroll
                     for (int u = 0; u < RB; ++u)
-                        old[u] = (need_prev && row + u < rows_valid)
+                        old[u] = (need_prev && row + u < row_hi)
                                      ? *(const uint32_t*)(pv + (size_t)(row + u) * (size_t)g.ldo) : 0u;
 #pragma unroll
                     for (int u = 0; u < RB; ++u) {
-                        if (row + u >= rows_valid) break;
+                        if (row + u >= row_hi) break;
                         const uint32_t v0 = k0 ? Cs[(row + u) * CP + r0] : (old[u] & 0xffffu);
                         const uint32_t v1 = k1 ? Cs[(row + u) * CP + r1] : (old[u] >> 16);
                         *(uint32_t*)(o + (size_t)(row + u) * (size_t)g.ldo) = v0 | (v1 << 16);
@@ -888,14 +898,14 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 const int side = own0 ? 0 : 1;
                 const bool kept = own0 ? k0 : k1;
                 const int rr = own0 ? r0 : r1;
-                for (int row = 0; row < rows_valid; row += RB) {
+                for (int row = row_lo; row < row_hi; row += RB) {
                     E old[RB];
 #pragma unroll
                     for (int u = 0; u < RB; ++u)
-                        old[u] = (!kept && row + u < rows_valid) ? pv[(size_t)(row + u) * (size_t)g.ldo + side] : E(0);
+                        old[u] = (!kept && row + u < row_hi) ? pv[(size_t)(row + u) * (size_t)g.ldo + side] : E(0);
 #pragma unroll
                     for (int u = 0; u < RB; ++u) {
-                        if (row + u >= rows_valid) break;
+                        if (row + u >= row_hi) break;
                         o[(size_t)(row + u) * (size_t)g.ldo + side] = kept ? Cs[(row + u) * CP + rr] : old[u];
                     }
                 }
