@@ -525,6 +525,7 @@ struct DmaP {
 #pragma unroll
         for (int q = 0; q < N; ++q) dma16(ptr[q] + c, stage + (wave + NW * q) * 256);
     }
+    __device__ __forceinline__ void settle(const FOp&) {}
 };
 
 // Contraction axis strided in memory (optional row list on it): LDS keeps the
@@ -542,9 +543,13 @@ struct DmaP {
 #ifndef ZR_QSWZ
 #define ZR_QSWZ 4
 #endif
-template <int R, int NT>
-struct DmaQ {
-    static constexpr const char* NAME = "DmaQ";
+// MAPPED: the memory rows go through a row list (W[S[c], :]).  A compile-time
+// property, because a run-time "list or identity" choice inside the loop leaves a
+// join whose register copies make the wavefront wait for every outstanding load,
+// the tile's direct-to-LDS loads included, before its first MFMA.
+template <int R, int NT, bool MAPPED>
+struct DmaQT {
+    static constexpr const char* NAME = MAPPED ? "DmaQM" : "DmaQ";
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
     static constexpr int RP = R <= 128 ? 128 : 256;
@@ -591,7 +596,9 @@ struct DmaQ {
         int idx[N];
 #pragma unroll
         for (int q = 0; q < N; ++q) idx[q] = min(c0 + tile_row(q, tid), C - 1);
-        lookup_rows<N>(op.map_s, op.n_s, idx, rr);
+        // with a list the entries are used as they arrive and clamped later, in settle()
+#pragma unroll
+        for (int q = 0; q < N; ++q) rr[q] = MAPPED ? op.map_s[idx[q]] : idx[q];
     }
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
@@ -606,6 +613,7 @@ struct DmaQ {
             colp[q] = op.base + min(r0 + chunk * 8, op.n_c - 8);     // the readable row length is a multiple of 8
         }
         rows_for(op, 0, C, tid);
+        settle(op);
     }
     __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
     {
@@ -617,7 +625,18 @@ struct DmaQ {
         }
         rows_for(op, c0 + BK, C, tid);
     }
+    // Called after the MFMAs of the step: the row-list entries requested by issue() have
+    // long arrived; clamping them here costs no wait and no time before the next issue.
+    __device__ __forceinline__ void settle(const FOp& op)
+    {
+        if constexpr (MAPPED) {
+#pragma unroll
+            for (int q = 0; q < N; ++q) rr[q] = clamp_idx(rr[q], op.n_s);
+        }
+    }
 };
+template <int R, int NT> using DmaQ = DmaQT<R, NT, false>;
+template <int R, int NT> using DmaQM = DmaQT<R, NT, true>;
 
 template <int AW, int BW_, int BM, int BN>
 constexpr int fast_smem_bytes()
@@ -684,6 +703,8 @@ __device__ __forceinline__ void pipeline_step(
         }
     }
     if (more) {
+        if constexpr (LA::DMA) la.settle(g.A);
+        if constexpr (LB::DMA) lb.settle(g.B);
         if constexpr (!LA::DMA) la.commit(g.A, wr, tid);
         if constexpr (!LB::DMA) lb.commit(g.B, wr + A_WORDS, tid);
         // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
@@ -787,6 +808,8 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         if constexpr (LB::DMA) lb.issue(g.B, stage + A_WORDS, kt * BK, g.C, tid); else lb.fetch(g.B, kt * BK, g.C, tid);
     };
     auto finish_tile = [&](uint32_t* stage) {
+        if constexpr (LA::DMA) la.settle(g.A);
+        if constexpr (LB::DMA) lb.settle(g.B);
         if constexpr (!LA::DMA) la.commit(g.A, stage, tid);
         if constexpr (!LB::DMA) lb.commit(g.B, stage + A_WORDS, tid);
         // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
@@ -858,10 +881,21 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             if (!g.prev) {
                 // dropped positions receive +0
                 if (own0 && own1) {
-                    for (int row = row_lo; row < row_hi; ++row) {
-                        const uint32_t v0 = k0 ? Cs[row * CP + r0] : 0u;
-                        const uint32_t v1 = k1 ? Cs[row * CP + r1] : 0u;
-                        *(uint32_t*)(o + (size_t)row * (size_t)g.ldo) = v0 | (v1 << 16);
+                    // 8 rows at a time: all LDS reads go out before the first store,
+                    // so the loop pays one LDS round trip per 8 rows
+                    constexpr int UB = 8;
+                    for (int row = row_lo; row < row_hi; row += UB) {
+                        uint32_t v[UB];
+#pragma unroll
+                        for (int u = 0; u < UB; ++u) {
+                            const int rr_ = min(row + u, row_hi - 1);
+                            const uint32_t v0 = k0 ? Cs[rr_ * CP + r0] : 0u;
+                            const uint32_t v1 = k1 ? Cs[rr_ * CP + r1] : 0u;
+                            v[u] = v0 | (v1 << 16);
+                        }
+#pragma unroll
+                        for (int u = 0; u < UB; ++u)
+                            if (row + u < row_hi) *(uint32_t*)(o + (size_t)(row + u) * (size_t)g.ldo) = v[u];
                     }
                 } else if (own0) {
                     for (int row = row_lo; row < row_hi; ++row)
@@ -1109,8 +1143,12 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     const bool b_zero = bg || (d.B.c_contig && d.B.zero_padded);
     const bool dma_ok = full_tiles || a_zero || b_zero;
     if (d.A.c_contig && !d.B.c_contig) {            // forward: X rows, W columns
-        if (!ag && !bg) return dma_ok ? launch_shape<DmaP, DmaQ>(a, stream) : launch_shape<LdPV, LdQV>(a, stream);
-        if (ag && !bg) return launch_shape<LdPG, DmaQ>(a, stream);
+        const bool bm = d.B.map_strided != nullptr;        // W[S[c], :]: the row list is on the contraction axis
+        if (!ag && !bg) {
+            if (!dma_ok) return launch_shape<LdPV, LdQV>(a, stream);
+            return bm ? launch_shape<DmaP, DmaQM>(a, stream) : launch_shape<DmaP, DmaQ>(a, stream);
+        }
+        if (ag && !bg) return bm ? launch_shape<LdPG, DmaQM>(a, stream) : launch_shape<LdPG, DmaQ>(a, stream);
         if (!ag && bg) return launch_shape<DmaP, LdQG>(a, stream);
         return -1;
     }
@@ -1120,7 +1158,8 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
         if (!ag && bg) return launch_shape<DmaP, LdPG>(a, stream);
         return -1;
     }
-    if (!d.A.c_contig && !d.B.c_contig) {           // dW
+    if (!d.A.c_contig && !d.B.c_contig) {           // dW: the contraction runs over the tokens, never through a list
+        if (d.A.map_strided || d.B.map_strided) return -1;
         if (!ag && !bg) return full_tiles ? launch_shape<DmaQ, DmaQ>(a, stream) : launch_shape<LdQV, LdQV>(a, stream);
         if (ag && !bg) return launch_shape<LdQG, DmaQ>(a, stream);
         if (!ag && bg) return launch_shape<DmaQ, LdQG>(a, stream);
