@@ -442,10 +442,11 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
             for (int b = 0; b < TN; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
-                    const int col = wc0 + b * 32 + l32;
-                    if (row < rows_in_tile && col < cols_in_tile)
-                        acc[a][b][r] = Ty<DT>::to_f32(old[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
+                    // coordinates clamped into the tile instead of a guard: the loads need no
+                    // branches and go out together; accumulators outside the tile are never stored
+                    const int row = min(wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3), rows_in_tile - 1);
+                    const int col = min(wc0 + b * 32 + l32, cols_in_tile - 1);
+                    acc[a][b][r] = Ty<DT>::to_f32(old[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
                 }
     }
 

@@ -769,6 +769,20 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     }
     if (LA::NEEDS_IDX || LB::NEEDS_IDX) __syncthreads();
 
+    // The scatter epilogues need the tile's entries of the kept list (one per thread)
+    // and the next tile's first entry.  They are requested here and only looked at
+    // after the main loop, so their latency never shows.
+    static_assert(BM <= NT && BN <= NT, "one kept-list entry per thread");
+    // (Unconditional loads: a conditional one would leave a join whose register copies
+    // wait for the load right here.  Without a scatter epilogue the address is any
+    // readable one, the output's first word, and the value is ignored.)
+    const bool scatter_c = g.epilogue == EPI_COL_SCATTER, scatter_r = g.epilogue == EPI_ROW_SCATTER;
+    const int k_first = scatter_c ? j0 : i0, k_count = scatter_c ? g.J : g.I, k_tile = scatter_c ? BN : BM;
+    const int32_t* k_list = (scatter_c || scatter_r) ? g.keep : (const int32_t*)g.out;
+    const int k_last = (scatter_c || scatter_r) ? k_count - 1 : 0;
+    const int keep_mine = k_list[min(k_first + tid, k_last)];
+    const int keep_next = k_list[min(k_first + k_tile, k_last)];
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
@@ -786,10 +800,11 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             for (int b = 0; b < TN; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
-                    const int col = wc0 + b * 32 + l32;
-                    if (row < rows_in_tile && col < cols_in_tile)
-                        acc[a][b][r] = bf16_bits_to_f32(g.out[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
+                    // coordinates clamped into the tile instead of a guard: the loads need no
+                    // branches and go out together; accumulators outside the tile are never stored
+                    const int row = min(wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3), rows_in_tile - 1);
+                    const int col = min(wc0 + b * 32 + l32, cols_in_tile - 1);
+                    acc[a][b][r] = bf16_bits_to_f32(g.out[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
                 }
     }
 
@@ -848,7 +863,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         // of RG row groups, consecutive threads on consecutive pairs: a tile owns
         // about BN / (1 - ratio) columns, i.e. fewer pairs than there are threads,
         // and the row groups keep every thread busy with a short loop.
-        for (int q = tid; q < cols_valid; q += NT) idxB[q] = clamp_idx(g.keep[j0 + q], g.out_full);
+        if (tid < cols_valid) idxB[tid] = clamp_idx(keep_mine, g.out_full);
         __syncthreads();
         if (g.avg_partial) {
             // sum of this tile's stored (rounded) results per output row, in column order
@@ -860,7 +875,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             }
         }
         const int start = j0 == 0 ? 0 : idxB[0];
-        const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(g.keep[j0 + BN], g.out_full);
+        const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(keep_next, g.out_full);
         constexpr int RG = 8;
         constexpr int ROWS_PER = (BM + RG - 1) / RG;
         const int first = start & ~1;
@@ -949,8 +964,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     }
 
     const bool scatter_rows = g.epilogue == EPI_ROW_SCATTER;
-    if (scatter_rows)
-        for (int q = tid; q < rows_valid; q += NT) idxA[q] = clamp_idx(g.keep[i0 + q], g.out_full);
+    if (scatter_rows && tid < rows_valid) idxA[tid] = clamp_idx(keep_mine, g.out_full);
     __syncthreads();
     if (scatter_rows && g.avg_partial) {
         // sum of this tile's stored (rounded) results per output column, in row order
@@ -971,7 +985,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     }
     if (scatter_rows) {
         const int start = i0 == 0 ? 0 : idxA[0];
-        const int end = i0 + BM >= g.I ? g.out_full : clamp_idx(g.keep[i0 + BM], g.out_full);
+        const int end = i0 + BM >= g.I ? g.out_full : clamp_idx(keep_next, g.out_full);
         for (int p = start + wave; p < end; p += NT / 64) {
             const int ii = lower_bound_lds(idxA, rows_valid, p);
             if (ii < rows_valid && idxA[ii] == p) continue;
