@@ -590,12 +590,22 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const KArgs g)
         // zero the dropped rows this tile owns (same ownership rule as above)
         const int start = i0 == 0 ? 0 : sidx[0];
         const int end = i0 + BM >= g.I ? g.out_full : clamp_idx(g.keep[i0 + BM], g.out_full);
-        for (int p = start + wave; p < end; p += NT / 64) {
-            const int ii = lower_bound_lds(sidx, rows_valid, p);
-            if (ii < rows_valid && sidx[ii] == p) continue;
-            E* o = out + (size_t)p * (size_t)g.ldo + j0;
-            const E* pv = prev ? prev + (size_t)p * (size_t)g.ldo + j0 : nullptr;
-            for (int j = lane; j < cols_valid; j += 64) o[j] = pv ? pv[j] : E(0);
+        // every lane looks one row up, the wavefront then writes the dropped ones together
+        for (int base = start + wave * 64; base < end; base += NT) {
+            const int mine = base + lane;
+            bool dropped = false;
+            if (mine < end) {
+                const int ii = lower_bound_lds(sidx, rows_valid, mine);
+                dropped = !(ii < rows_valid && sidx[ii] == mine);
+            }
+            unsigned long long todo = __ballot(dropped);
+            while (todo) {
+                const int p = base + (__ffsll((long long)todo) - 1);
+                todo &= todo - 1;
+                E* o = out + (size_t)p * (size_t)g.ldo + j0;
+                const E* pv = prev ? prev + (size_t)p * (size_t)g.ldo + j0 : nullptr;
+                for (int j = lane; j < cols_valid; j += 64) o[j] = pv ? pv[j] : E(0);
+            }
         }
     }
 }

@@ -986,15 +986,27 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     if (scatter_rows) {
         const int start = i0 == 0 ? 0 : idxA[0];
         const int end = i0 + BM >= g.I ? g.out_full : clamp_idx(keep_next, g.out_full);
-        for (int p = start + wave; p < end; p += NT / 64) {
-            const int ii = lower_bound_lds(idxA, rows_valid, p);
-            if (ii < rows_valid && idxA[ii] == p) continue;
-            E* o = out + (size_t)p * (size_t)g.ldo + j0;
-            if (!g.prev) {
-                for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = zero4();
-            } else {
-                const E* pv = g.prev + (size_t)p * (size_t)g.ldo + j0;
-                for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = *(const uint4*)(pv + j);
+        // Which of the rows [start, end) are dropped: every lane looks one row up (64
+        // searches side by side instead of one after the other), then the wavefront
+        // walks the set bits of the ballot and writes each dropped row together.
+        for (int base = start + wave * 64; base < end; base += NT) {
+            const int mine = base + lane;
+            bool dropped = false;
+            if (mine < end) {
+                const int ii = lower_bound_lds(idxA, rows_valid, mine);
+                dropped = !(ii < rows_valid && idxA[ii] == mine);
+            }
+            unsigned long long todo = __ballot(dropped);
+            while (todo) {
+                const int p = base + (__ffsll((long long)todo) - 1);
+                todo &= todo - 1;
+                E* o = out + (size_t)p * (size_t)g.ldo + j0;
+                if (!g.prev) {
+                    for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = zero4();
+                } else {
+                    const E* pv = g.prev + (size_t)p * (size_t)g.ldo + j0;
+                    for (int j = lane * 8; j < cols_valid; j += 64 * 8) *(uint4*)(o + j) = *(const uint4*)(pv + j);
+                }
             }
         }
     }
