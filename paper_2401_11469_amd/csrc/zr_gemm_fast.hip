@@ -846,24 +846,112 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int rows_valid = min(BM, g.I - i0);
     const int cols_valid = min(BN, g.J - j0);
     E* out = g.out;
+    // accumulators -> C tile in LDS, one column per kept index ("compacted")
+    auto stage_compacted = [&] {
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
+        for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TN; ++b)
+            for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
-                Cs[row * CP + wc0 + b * 32 + l32] = to_bf16(acc[a][b][r]);
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
+                    Cs[row * CP + wc0 + b * 32 + l32] = to_bf16(acc[a][b][r]);
+                }
+    };
 
     if (g.epilogue == EPI_COL_SCATTER) {
         // The tile owns the original columns from its first kept column (0 for the
         // first tile) up to the next tile's first kept column (the full width for
-        // the last one).  Work item <-> one aligned pair of original columns over one
-        // of RG row groups, consecutive threads on consecutive pairs: a tile owns
-        // about BN / (1 - ratio) columns, i.e. fewer pairs than there are threads,
-        // and the row groups keep every thread busy with a short loop.
+        // the last one).
         if (tid < cols_valid) idxB[tid] = clamp_idx(keep_mine, g.out_full);
+        __syncthreads();
+        const int start = j0 == 0 ? 0 : idxB[0];
+        const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(keep_next, g.out_full);
+
+        // Main form: the tile is laid out in LDS the way it lies in memory, one LDS
+        // column per ORIGINAL column from `start` (rounded down to a 16-byte chunk) to
+        // `end`, half of the tile's rows at a time.  The rows are first filled with the
+        // imputed value (+0, or the previous tensor's 16-byte chunks), then every
+        // accumulator is written at its original column, then the rows leave with
+        // whole 16-byte stores like a plain tile; only the first and last chunk, which
+        // the tile shares with its neighbours, are stored element by element.
+        constexpr int HR = BM / 2;
+        static_assert(HR % 32 == 0, "a 32-row MFMA block must lie in one half");
+        constexpr int MAIN_HALFWORDS = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN>() - (BM + BN) * 4) / 2;
+        const int a0 = start & ~7;
+        const int nchunks = (((end + 7) & ~7) - a0) >> 3;
+        const int pitch = nchunks * 8 + 8;
+        if (g.out_full % 8 == 0 && HR * pitch <= MAIN_HALFWORDS) {
+            E* Co = (E*)smem;
+            int pos[TN];                       // LDS column of this lane's accumulators, -1 beyond the tile
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int col = wc0 + b * 32 + l32;
+                // (clamped into the row: a list that is not ascending must not leave the tile)
+                pos[b] = col < cols_valid ? min(max(idxB[col] - a0, 0), nchunks * 8 - 1) : -1;
+            }
+            for (int h = 0; h < 2; ++h) {
+                const int hr0 = h * HR;
+                const int hrows = min(HR, rows_valid - hr0);
+                if (hrows <= 0) break;
+                for (int u = tid; u < hrows * nchunks; u += NT) {
+                    const int r = u / nchunks, c = u - r * nchunks;
+                    uint4 v = zero4();
+                    if (g.prev) v = *(const uint4*)(g.prev + (size_t)(i0 + hr0 + r) * (size_t)g.ldo + a0 + c * 8);
+                    *(uint4*)(Co + r * pitch + c * 8) = v;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+                    if ((wr0 + a * 32) / HR != h) continue;
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        if (pos[b] < 0) continue;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3) - hr0;
+                            Co[row * pitch + pos[b]] = to_bf16(acc[a][b][r]);
+                        }
+                    }
+                }
+                __syncthreads();
+                if (g.avg_partial) {
+                    // sum of the row's stored (rounded) results; the imputed zeros add nothing
+                    float* dst = g.avg_partial + (size_t)(g.avg_slot_base + tj) * (size_t)g.avg_len + i0 + hr0;
+                    for (int r = tid; r < hrows; r += NT) {
+                        float sum = 0.f;
+                        for (int c = start - a0; c < end - a0; ++c) sum += bf16_bits_to_f32(Co[r * pitch + c]);
+                        dst[r] = sum;
+                    }
+                }
+                for (int u = tid; u < hrows * nchunks; u += NT) {
+                    const int r = u / nchunks, c = u - r * nchunks;
+                    const int p = a0 + c * 8;
+                    E* o = out + (size_t)(i0 + hr0 + r) * (size_t)g.ldo + p;
+                    const E* src = Co + r * pitch + c * 8;
+                    if (p >= start && p + 8 <= end) *(uint4*)o = *(const uint4*)src;
+                }
+                // the first and the last chunk are shared with the neighbouring tiles: their
+                // owned elements go out one by one, one work item per (row, element), so
+                // that no wavefront serialises on a few lanes
+                const int e1_lo = start, e1_hi = (a0 < start || a0 + 8 > end) ? min(end, a0 + 8) : start;
+                const int last = a0 + (nchunks - 1) * 8;
+                const int e2_lo = max(start, last), e2_hi = (nchunks > 1 && last + 8 > end) ? end : e2_lo;
+                const int n1 = e1_hi - e1_lo, ne = n1 + (e2_hi - e2_lo);
+                for (int u = tid; u < hrows * ne; u += NT) {
+                    const int r = u / ne, e = u - r * ne;
+                    const int p = e < n1 ? e1_lo + e : e2_lo + (e - n1);
+                    out[(size_t)(i0 + hr0 + r) * (size_t)g.ldo + p] = Co[r * pitch + p - a0];
+                }
+                __syncthreads();               // the next half reuses the rows
+            }
+            return;
+        }
+
+        // Fallback for tiles that own too many columns for the layout above (sparse kept
+        // sets): compacted C tile; work item <-> one aligned pair of original columns
+        // over one of RG row groups, consecutive threads on consecutive pairs.
+        stage_compacted();
         __syncthreads();
         if (g.avg_partial) {
             // sum of this tile's stored (rounded) results per output row, in column order
@@ -874,8 +962,6 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 dst[row] = sum;
             }
         }
-        const int start = j0 == 0 ? 0 : idxB[0];
-        const int end = j0 + BN >= g.J ? g.out_full : clamp_idx(keep_next, g.out_full);
         constexpr int RG = 8;
         constexpr int ROWS_PER = (BM + RG - 1) / RG;
         const int first = start & ~1;
@@ -963,6 +1049,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         return;
     }
 
+    stage_compacted();
     const bool scatter_rows = g.epilogue == EPI_ROW_SCATTER;
     if (scatter_rows && tid < rows_valid) idxA[tid] = clamp_idx(keep_mine, g.out_full);
     __syncthreads();
