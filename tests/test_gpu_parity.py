@@ -469,6 +469,34 @@ def test_average_through_the_epilogue_sums(zr, torch_mod, oracle, dtype, mode, M
         check_layer(oracle, case, S, mode, dtype, AVERAGE, b)
 
 
+@pytest.mark.parametrize("policy", [ZERO, SAME, AVERAGE])
+def test_fast_kernels_with_an_output_width_that_is_not_a_chunk_multiple(zr, torch_mod, oracle, policy):
+    """Column-parallel shard stored [N x K] with N = 300: every leading dimension is a multiple
+    of 8 (the fast kernels apply) but the scattered width is not, so the column-scatter
+    epilogue must not touch whole 16-byte chunks at the row ends."""
+    torch = torch_mod
+    M, K, N = 270, 520, 300
+    case = wl.random_case(9090, M, K, N, "bf16")
+    X = to_gpu(torch, case["X"], "bf16")
+    Wt = to_gpu(torch, np.ascontiguousarray(case["W"].T), "bf16")
+    dY = to_gpu(torch, case["dY"], "bf16", ld=304)
+    for n_keep in (N - 1, 200, 3):
+        S = subset(n_keep + 11, N, n_keep)
+        keep = idx_gpu(torch, S)
+        pY = to_gpu(torch, case["prev_Y"], "bf16", ld=304) if policy == SAME else None
+        pdW = to_gpu(torch, np.ascontiguousarray(case["prev_dW"].T), "bf16") if policy == SAME else None
+        Y = to_gpu(torch, np.full((M, N), 555.0, np.float32), "bf16", ld=304)
+        dX = to_gpu(torch, np.full((M, K), 555.0, np.float32), "bf16")
+        dWt = to_gpu(torch, np.full((N, K), 555.0, np.float32), "bf16")
+        ws = torch.empty(zr.workspace_bytes(M, K, N, n_keep, DROP_N, torch.bfloat16), dtype=torch.uint8, device="cuda")
+        zr.resized_linear_fwd(X, Wt, keep, DROP_N, policy, pY, Y=Y, workspace=ws, w_layout=W_NK)
+        assert zr.debug_last_kernel().startswith("fast_kernel")
+        zr.resized_linear_bwd(X, Wt, dY, keep, DROP_N, policy, None, pdW, dX=dX, dW=dWt, workspace=ws, w_layout=W_NK)
+        torch.cuda.synchronize()
+        assert torch.all(Y._base[:, N:] == 777.0), "padding overwritten"
+        check_layer(oracle, case, S, DROP_N, "bf16", policy, (to_np(Y), to_np(dX), to_np(dWt).T))
+
+
 def test_contiguous_and_extreme_kept_sets(zr, torch_mod, oracle):
     """Kept sets that are a prefix, a suffix, every other index, or one far
     index: the scatter epilogue's ownership ranges degenerate in each."""
