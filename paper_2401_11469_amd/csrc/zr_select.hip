@@ -8,17 +8,20 @@
 // those equal to T, writing kept and pruned indices by prefix position, which
 // makes both lists ascending by construction.
 //
-// One workgroup of 1024 threads (16 wavefronts of 64) per score vector.  Vectors
-// of up to 12288 scores are turned into order keys once and kept in LDS, so
-// the five passes read HBM a single time; longer ones re-read from memory.
+// One workgroup per score vector: 1024 threads (16 wavefronts of 64) for a single
+// vector, where latency is what counts, 256 threads when many vectors are
+// selected in one launch, so that 8 of them share a compute unit and the chip's
+// memory system stays busy.  Vectors of up to 12288 scores are turned into order
+// keys once and kept in LDS (sized to the vector), so the five passes read HBM a
+// single time; longer ones re-read from memory.
 #include "zr_common.h"
 
 namespace zr {
 
 namespace {
 
-constexpr int SEL_THREADS = 1024;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_THREADS = 1024;      // single vector
+constexpr int SEL_THREADS_MANY = 256;  // many vectors per launch
 
 // Monotone map fp32 -> uint32: larger score <=> larger key.  NaN -> 0 (lowest,
 // below -inf); -0.0 and +0.0 share one key.
@@ -33,11 +36,13 @@ __device__ __forceinline__ uint32_t order_key(float s)
 constexpr int SEL_LDS_KEYS = 12288;    // 48 KB of order keys
 
 // One workgroup selects one score vector s[n]: keep[n_keep] and drop[n - n_keep].
-template <bool STAGED>
+template <bool STAGED, int NT>
 __device__ __forceinline__ void select_body(const float* __restrict__ s, int n, int n_keep,
                                             int32_t* __restrict__ keep, int32_t* __restrict__ drop)
 {
-    __shared__ uint32_t keys[STAGED ? SEL_LDS_KEYS : 1];
+    constexpr int SEL_WAVES = NT / 64;
+    static_assert(NT >= 256 && NT % 64 == 0, "the histogram is cleared by the first 256 threads");
+    extern __shared__ uint32_t keys[];            // n order keys when STAGED (dynamic size)
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_digit, s_remaining;
     __shared__ uint32_t wave_gt[SEL_WAVES], wave_eq[SEL_WAVES];
@@ -47,7 +52,7 @@ __device__ __forceinline__ void select_body(const float* __restrict__ s, int n, 
     const int wave = tid >> 6;
 
     if (STAGED) {
-        for (int i = tid; i < n; i += SEL_THREADS) keys[i] = order_key(s[i]);
+        for (int i = tid; i < n; i += NT) keys[i] = order_key(s[i]);
         __syncthreads();
     }
     auto key_at = [&](int i) -> uint32_t { return STAGED ? keys[i] : order_key(s[i]); };
@@ -58,7 +63,7 @@ __device__ __forceinline__ void select_body(const float* __restrict__ s, int n, 
         const int shift = 24 - 8 * pass;
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += SEL_THREADS) {
+        for (int i = tid; i < n; i += NT) {
             const uint32_t k = key_at(i);
             if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
         }
@@ -97,7 +102,7 @@ __device__ __forceinline__ void select_body(const float* __restrict__ s, int n, 
 
     // ---- ordered compaction -----------------------------------------------
     uint32_t run_gt = 0, run_eq = 0;    // totals over all earlier chunks
-    for (int base = 0; base < n; base += SEL_THREADS) {
+    for (int base = 0; base < n; base += NT) {
         const int i = base + tid;
         bool gt = false, eq = false;
         if (i < n) {
@@ -142,12 +147,12 @@ __device__ __forceinline__ void select_body(const float* __restrict__ s, int n, 
     }
 }
 
-template <bool STAGED>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+template <bool STAGED, int NT>
+__global__ __launch_bounds__(NT) void select_kernel(
     const float* __restrict__ scores, int n, int n_keep,
     int32_t* __restrict__ keep_idx, int32_t* __restrict__ drop_idx, int64_t ld_idx)
 {
-    select_body<STAGED>(scores + (size_t)blockIdx.x * (size_t)n, n, n_keep,
+    select_body<STAGED, NT>(scores + (size_t)blockIdx.x * (size_t)n, n, n_keep,
                         keep_idx + (size_t)blockIdx.x * (size_t)ld_idx,
                         drop_idx ? drop_idx + (size_t)blockIdx.x * (size_t)ld_idx : nullptr);
 }
@@ -159,7 +164,7 @@ template <bool STAGED>
 __global__ __launch_bounds__(SEL_THREADS) void select_multi_kernel(const SelectMulti m)
 {
     const int b = blockIdx.x;
-    select_body<STAGED>(m.scores[b], m.n[b], m.n_keep[b], m.keep[b], m.drop[b]);
+    select_body<STAGED, SEL_THREADS>(m.scores[b], m.n[b], m.n_keep[b], m.keep[b], m.drop[b]);
 }
 
 __global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
@@ -180,21 +185,27 @@ __global__ void validate_kernel(const int32_t* __restrict__ keep_idx, int n_keep
 int launch_select(const float* scores, int n, int batch, int n_keep,
                   int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream)
 {
-    if (n <= SEL_LDS_KEYS)
-        hipLaunchKernelGGL(select_kernel<true>, dim3(batch), dim3(SEL_THREADS), 0, stream,
+    const size_t key_bytes = (size_t)n * sizeof(uint32_t);
+    if (n > SEL_LDS_KEYS)
+        hipLaunchKernelGGL((select_kernel<false, SEL_THREADS>), dim3(batch), dim3(SEL_THREADS), 0, stream,
                            scores, n, n_keep, keep_idx, drop_idx, ld_idx);
+    else if (batch >= 512)      // two workgroups per compute unit and more: throughput over latency
+        hipLaunchKernelGGL((select_kernel<true, SEL_THREADS_MANY>), dim3(batch), dim3(SEL_THREADS_MANY), key_bytes,
+                           stream, scores, n, n_keep, keep_idx, drop_idx, ld_idx);
     else
-        hipLaunchKernelGGL(select_kernel<false>, dim3(batch), dim3(SEL_THREADS), 0, stream,
+        hipLaunchKernelGGL((select_kernel<true, SEL_THREADS>), dim3(batch), dim3(SEL_THREADS), key_bytes, stream,
                            scores, n, n_keep, keep_idx, drop_idx, ld_idx);
     return hip_status(hipGetLastError());
 }
 
 int launch_select_multi(const SelectMulti& m, int count, hipStream_t stream)
 {
-    bool staged = true;
-    for (int b = 0; b < count; ++b) staged = staged && m.n[b] <= SEL_LDS_KEYS;
+    int longest = 0;
+    for (int b = 0; b < count; ++b) longest = std::max(longest, m.n[b]);
+    const bool staged = longest <= SEL_LDS_KEYS;
     if (staged)
-        hipLaunchKernelGGL(select_multi_kernel<true>, dim3(count), dim3(SEL_THREADS), 0, stream, m);
+        hipLaunchKernelGGL(select_multi_kernel<true>, dim3(count), dim3(SEL_THREADS),
+                           (size_t)longest * sizeof(uint32_t), stream, m);
     else
         hipLaunchKernelGGL(select_multi_kernel<false>, dim3(count), dim3(SEL_THREADS), 0, stream, m);
     return hip_status(hipGetLastError());

@@ -101,6 +101,24 @@ def test_select_special_values_and_batch(zr, torch_mod, oracle):
     assert keep[3].cpu().numpy().tolist() == list(range(oracle.keep_count(n, 0.35)))
 
 
+@pytest.mark.parametrize("n,ratio", [(1000, 0.3), (4096, 0.05), (12288, 0.5), (13000, 0.25)])
+def test_select_many_vectors_in_one_launch(zr, torch_mod, oracle, n, ratio):
+    """From 512 vectors on, a launch uses the small-workgroup variant (several vectors
+    per compute unit); every vector must still match the oracle bit for bit."""
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(n))
+    B = 600
+    S = g.standard_normal((B, n)).astype(np.float32)
+    S[:, ::7] = np.round(S[:, ::7], 1)          # plenty of ties
+    S[5, :] = -2.0
+    S[6, 1::3] = np.nan
+    keep, drop = zr.resize_select(torch.from_numpy(S).cuda(), ratio)
+    keep, drop = keep.cpu().numpy(), drop.cpu().numpy()
+    for b in range(0, B, 7):
+        ok, od = oracle.resize_select(S[b], ratio)
+        assert np.array_equal(keep[b], ok) and np.array_equal(drop[b], od)
+
+
 def test_select_on_config_scores(zr, torch_mod, oracle):
     torch = torch_mod
     for cid, cfg in wl.CONFIGS.items():
