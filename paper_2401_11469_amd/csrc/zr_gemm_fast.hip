@@ -8,19 +8,25 @@
 // How each kept-index gather of the resized products (paper Sec. 3.1) is fused
 // into the load path, none of them through sub-dword global loads (those run
 // at ~4 lanes/clk on this chip):
-//   rows of a tensor (W[S,:])            -> the row list only changes the row
-//        pointer of ordinary 16-byte loads (loaders PV / QV).
-//   contiguous axis, non-contraction     -> (W[:,S] in forward, X[:,S] and
-//        dY[:,S] in dW) the full-width span of the tile's kept columns is
-//        fetched with 16-byte loads, two memory rows are interleaved into
-//        (c, c+1) words in registers, and only the kept columns' words are
-//        written to LDS, at their compacted positions (loader QG).
-//   contiguous axis, contraction         -> (X[:,S] in forward DROP_K, dY[:,S]
-//        and W[:,S] in dX DROP_N) each LDS word (two consecutive kept indices
-//        of one row) is assembled from two aligned dword loads with one byte
-//        permute (loader PG).
-// The epilogue composes full-width output rows in LDS order: kept columns get
-// their result, dropped columns of the tile's span get +0, stored as dwords.
+//   rows of a stored matrix (W[S,:], or any kept slice of a shard stored in the
+//        layout that makes it rows) -> the row list only changes the row pointer
+//        of the direct-to-LDS loads (loaders DmaP; DmaQM when the list runs
+//        along the contraction axis and is walked tile by tile).
+//   plain operands, and activations whose kept columns the caller's scratch
+//        buffer already holds compacted -> direct-to-LDS loads (DmaP / DmaQ).
+//   contiguous axis, non-contraction, no scratch -> the full-width span of the
+//        tile's kept columns is fetched with 16-byte loads, memory rows are
+//        interleaved in registers and only the kept columns' words are written to
+//        LDS at their compacted positions (loader LdQG).
+//   contiguous axis, contraction, no scratch -> each LDS word (two consecutive
+//        kept indices of one row) is assembled from two aligned dword loads with
+//        one byte permute (loader LdPG).
+//   LdPV / LdQV: register-staged plain loaders for contraction extents that are
+//        not a multiple of 64 when no operand supplies the zero tail.
+// Epilogues: plain 16-byte stores; row scatter (kept rows to their original
+// rows, dropped rows imputed); column scatter (the tile is laid out by original
+// column in LDS, imputed value first, results on top, 16-byte stores).  Zero and
+// Same imputation happen here; Average leaves per-tile sums for a fill pass.
 #include <cstdio>
 
 #include "zr_common.h"
