@@ -126,8 +126,9 @@ def main() -> int:
             full = keep.numel() == p["n"]
             if events is None:
                 zr.resized_linear_fwd(p["X"], p["W"], keep, pr.mode, Y=p["Y"], workspace=ws, w_layout=p["layout"])
+                # the scratch buffer still holds what this projection's forward extracted
                 zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=ws,
-                                      w_layout=p["layout"])
+                                      w_layout=p["layout"], workspace_holds_forward=True)
             else:
                 # one event pair per product, recorded by the library right around the
                 # product's own GEMM launch(es) (zr_debug_time_next_product), so that an
@@ -145,7 +146,7 @@ def main() -> int:
                                               workspace=ws, w_layout=p["layout"])
                     else:
                         zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, pr.mode, dW=p["dW"], need_dX=False,
-                                              workspace=ws, w_layout=p["layout"])
+                                              workspace=ws, w_layout=p["layout"], workspace_holds_forward=True)
                     events.append((zr.debug_last_kernel(), fl, e0, e1))
                 if ws is not None and not full and tdt == torch.bfloat16:
                     src = p["X"] if pr.mode == zr.DROP_K else p["dY"]
@@ -316,7 +317,8 @@ def main() -> int:
                                + ", ".join(f"{p.name}[{p.K}x{p.N}]{p.parallel}" for p in cfg.projections)
                                + "; per-step ratio drawn (seeded) from " + str(list(cfg.ratios)),
                    "path": "resize_select_multi (one launch for the 5 projections) + resized_linear_fwd + resized_linear_bwd(dX,dW), Zero imputation, "
-                           "with the optional scratch buffer for the extracted kept columns of activations; column-parallel shards "
+                           "with the optional scratch buffer for the extracted kept columns of activations (the backward call reuses "
+                           "what the forward call of the same projection extracted); column-parallel shards "
                            "stored [N x K], row-parallel [K x N] (the kept list selects rows of the stored weight, no weight copy)"},
         "frac_mfma_peak": value / peak,
         "gpu_ms_per_step": gpu_ms / args.steps, "wall_ms_per_step": wall * 1e3 / args.steps,

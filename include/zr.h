@@ -77,6 +77,15 @@ typedef enum { ZR_DROP_N = 0, ZR_DROP_K = 1 } zr_mode;
  * row-parallel shards as KN and column-parallel shards as NK. */
 typedef enum { ZR_W_KN = 0, ZR_W_NK = 1 } zr_w_layout;
 
+/* Flags of the backward call's workspace.
+ *  ZR_WS_HOLDS_FORWARD: the buffer is the one the forward call of the SAME layer
+ *  step was given (same X, keep_idx, sizes, mode, dtype) and nothing has written
+ *  to it since: what the forward extracted (X[:,S] in DROP_K) is used again
+ *  instead of being extracted a second time; this is the pruned input that the
+ *  paper's layer keeps for its backward pass (Sec. 3.1).  Without the flag the
+ *  backward call extracts what it needs itself.  Results are identical. */
+typedef enum { ZR_WS_FRESH = 0, ZR_WS_HOLDS_FORWARD = 1 } zr_ws_flags;
+
 /* Imputation policies of Sec. 3.1 ("what value should be imputed"). */
 typedef enum {
     ZR_IMPUTE_ZERO = 0,     /* +0.0 (the paper's final choice) */
@@ -169,7 +178,7 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
  *  dX [M x K] lddx and dW (stored like W: [K x N] or [N x K], lddw) are outputs;
  *  either may be NULL to skip that product.  prev_dX / prev_dW (same shapes,
  *  layout and leading dimensions as dX / dW) are read for ZR_IMPUTE_SAME only.
- *  workspace: as for the forward call.
+ *  workspace: as for the forward call; workspace_flags: see zr_ws_flags (0 = none).
  *  Errors as for the forward call. */
 int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw,
                           const void* dY, int64_t lddy,
@@ -178,7 +187,7 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           const int32_t* keep_idx, int32_t n_keep,
                           int mode, int w_layout, int dtype, int policy,
                           const void* prev_dX, const void* prev_dW,
-                          void* workspace, size_t workspace_bytes, void* stream);
+                          void* workspace, size_t workspace_bytes, int workspace_flags, void* stream);
 
 /* Stand-alone recovery/imputation (Sec. 3.1, "Our solution is to add missing
  * dimensions" and the three policies): fills every slice of out[rows x cols]

@@ -271,7 +271,7 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           const int32_t* keep_idx, int32_t n_keep,
                           int mode, int w_layout, int dtype, int policy,
                           const void* prev_dX, const void* prev_dW,
-                          void* workspace, size_t workspace_bytes, void* stream)
+                          void* workspace, size_t workspace_bytes, int workspace_flags, void* stream)
 {
     if (!dY || (!dX && !dW)) return ZR_ERR_NULL;
     if ((dX && !W) || (dW && !X)) return ZR_ERR_NULL;
@@ -303,7 +303,10 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     Extract ex{false, 0};
     if (mode == ZR_DROP_K) {
         if (dW) ex = plan_extract(X, ldx, M, K, n_keep, dtype, workspace, workspace_bytes);
-        if (ex.use) st = launch_compact_cols(X, ldx, M, K, keep_idx, n_keep, workspace, ex.width, ex.width, s);
+        // the forward call of this layer left X[:,S] at the same place (same plan, same sizes)
+        const bool reuse = (workspace_flags & ZR_WS_HOLDS_FORWARD) != 0;
+        if (ex.use && !reuse)
+            st = launch_compact_cols(X, ldx, M, K, keep_idx, n_keep, workspace, ex.width, ex.width, s);
     } else {
         ex = plan_extract(dY, lddy, M, N, n_keep, dtype, workspace, workspace_bytes);
         if (ex.use) st = launch_compact_cols(dY, lddy, M, N, keep_idx, n_keep, workspace, ex.width, ex.width, s);

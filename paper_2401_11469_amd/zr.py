@@ -15,6 +15,7 @@ import torch
 
 DROP_N, DROP_K = 0, 1
 W_KN, W_NK = 0, 1
+WS_FRESH, WS_HOLDS_FORWARD = 0, 1
 ZERO, AVERAGE, SAME = 0, 1, 2
 F32, BF16 = 0, 1
 
@@ -42,7 +43,7 @@ _lib.zr_resized_linear_fwd.restype = ctypes.c_int
 _lib.zr_resized_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                        _i32, _i32, _i32, _vp, _i32,
                                        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
-                                       _vp, ctypes.c_size_t, _vp]
+                                       _vp, ctypes.c_size_t, ctypes.c_int, _vp]
 _lib.zr_resized_linear_bwd.restype = ctypes.c_int
 _lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, ctypes.c_int, _vp]
 _lib.zr_impute.restype = ctypes.c_int
@@ -208,8 +209,10 @@ def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_
                        prev_dW: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
                        dW: Optional[torch.Tensor] = None, need_dX: bool = True, need_dW: bool = True,
                        workspace: Optional[torch.Tensor] = None, stream=None,
-                       w_layout: int = W_KN) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
-    """W and dW are [K, N] (w_layout=W_KN) or [N, K] (W_NK)."""
+                       w_layout: int = W_KN,
+                       workspace_holds_forward: bool = False) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """W and dW are [K, N] (w_layout=W_KN) or [N, K] (W_NK).  workspace_holds_forward: the
+    workspace is the one the forward call of this layer step used and is untouched since."""
     M, K = X.shape
     N = dY.shape[1]
     wshape = (K, N) if w_layout == W_KN else (N, K)
@@ -226,7 +229,8 @@ def resized_linear_bwd(X: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, keep_
         raise ValueError("previous tensors must share the outputs' leading dimensions")
     _check(_lib.zr_resized_linear_bwd(xp, ldx, wp, ldw, gp, ldg, dxp, lddx, dwp, lddw, M, K, N,
                                       keep_idx.data_ptr(), keep_idx.numel(), mode, w_layout, _dtype_code(X),
-                                      policy, pxp, pwp, *_ws(workspace), _stream(stream)))
+                                      policy, pxp, pwp, *_ws(workspace), 1 if workspace_holds_forward else 0,
+                                      _stream(stream)))
     return (dX if need_dX else None), (dW if need_dW else None)
 
 

@@ -146,8 +146,8 @@ def test_argument_validation_returns_before_any_gpu_work(lib):
     assert ext(p, 7, 4, 7, p, 4, p, 64, 1, None) == 2          # odd row length
     bwd = lib.zr_resized_linear_bwd
     bwd.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, i32,
-                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
     bwd.restype = ctypes.c_int
-    assert bwd(p, 8, p, 8, p, 8, None, 8, None, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, None) == 1
-    assert bwd(p, 8, p, 8, p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, None) == 2
-    assert bwd(p, 8, p, 8, p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 1, 0, 1, 2, None, None, None, 0, None) == 7
+    assert bwd(p, 8, p, 8, p, 8, None, 8, None, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, 0, None) == 1
+    assert bwd(p, 8, p, 8, p, 4, p, 8, p, 8, 4, 8, 8, p, 4, 0, 0, 1, 0, None, None, None, 0, 0, None) == 2
+    assert bwd(p, 8, p, 8, p, 8, p, 8, p, 8, 4, 8, 8, p, 4, 1, 0, 1, 2, None, None, None, 0, 0, None) == 7

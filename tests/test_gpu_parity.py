@@ -578,6 +578,29 @@ def test_workspace_path_matches_oracle_and_in_flight_path(zr, torch_mod, oracle,
         check_layer(oracle, case, S, mode, "bf16", policy, got)
 
 
+@pytest.mark.parametrize("policy", [ZERO, AVERAGE])
+def test_backward_reuses_what_the_forward_extracted(zr, torch_mod, oracle, policy):
+    """DROP_K: the forward leaves X[:,S] in the scratch buffer; a backward call that is told
+    so must give the results of one that extracts again, bit for bit."""
+    torch = torch_mod
+    M, K, N = 300, 520, 392
+    case = wl.random_case(4711, M, K, N, "bf16")
+    S = subset(8, K, (2 * K) // 3)
+    keep = idx_gpu(torch, S)
+    X, W, dY = (to_gpu(torch, case[k], "bf16") for k in ("X", "W", "dY"))
+    ws = torch.full((zr.workspace_bytes(M, K, N, len(S), DROP_K, torch.bfloat16),), 0x7F, dtype=torch.uint8, device="cuda")
+    outs = []
+    for reuse in (False, True):
+        ws.fill_(0x7F)
+        Y = zr.resized_linear_fwd(X, W, keep, DROP_K, policy, workspace=ws)
+        dX, dW = zr.resized_linear_bwd(X, W, dY, keep, DROP_K, policy, workspace=ws, workspace_holds_forward=reuse)
+        torch.cuda.synchronize()
+        outs.append((to_np(Y), to_np(dX), to_np(dW)))
+    check_layer(oracle, case, S, DROP_K, "bf16", policy, outs[1])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
 def test_bitwise_repeatable(zr, torch_mod):
     torch = torch_mod
     case = wl.random_case(5, 300, 520, 390, "bf16")
