@@ -1156,11 +1156,17 @@ struct Sched {
 inline int64_t tiles_of(int I, int J, int bm, int bn) { return (int64_t)((I + bm - 1) / bm) * ((J + bn - 1) / bn); }
 inline double cost_192(int64_t tiles) { return ZR_COST_192 * (double)((tiles + 255) / 256); }
 
+#ifndef ZR_COST_SMALL1
+#define ZR_COST_SMALL1 0.42
+#endif
+#ifndef ZR_COST_SMALL2
+#define ZR_COST_SMALL2 0.70
+#endif
 inline double small_cost(int64_t ts)
 {
     if (ts <= 0) return 0.0;
-    if (ts <= 256) return 0.42;                       // one small tile per CU
-    return 0.70 * (double)((ts + 511) / 512);         // two per CU
+    if (ts <= 256) return ZR_COST_SMALL1;                       // one small tile per CU
+    return ZR_COST_SMALL2 * (double)((ts + 511) / 512);         // two per CU
 }
 
 inline Sched plan_tiles(int I, int J)
