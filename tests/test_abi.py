@@ -92,6 +92,22 @@ def test_migration_range_host_function(lib, oracle):
     assert f(0, 0, 2, 4, None, ctypes.byref(e_)) != 0
 
 
+def test_direct_to_lds_gemm_kernels_do_not_spill():
+    """The build leaves the compiler's per-kernel resource figures next to the library.  The
+    kernels the benchmark runs (both loaders direct-to-LDS) must not use scratch memory: a
+    spilling main loop costs 15-20 % without failing any numerical test."""
+    import re
+    from paper_2401_11469_amd import build
+    if not os.path.exists(build.RESOURCES):
+        pytest.skip("no resource table (library not built by build.py here)")
+    rows = [l.split(" | ") for l in open(build.RESOURCES) if not l.startswith("#")]
+    fast = [r for r in rows if re.match(r"fast_kernel<Dma\w+, Dma\w+,", r[0])]
+    assert len(fast) >= 12, "expected the direct-to-LDS instantiations in the table"
+    for name, vgpr, agpr, scratch, occ, lds in fast:
+        assert int(scratch) == 0, (name, scratch)
+        assert int(lds) <= 160 * 1024, (name, lds)
+
+
 def test_status_strings(lib):
     f = lib.zr_status_string
     f.argtypes = [ctypes.c_int]
