@@ -285,6 +285,14 @@ def main() -> int:
     aux["priority_scores"] = pri
     cnt = torch.empty(1, dtype=torch.int32, device=dev)
     aux["count_above_us"] = timed(lambda: zr.count_above(p0["scores"], 0.5, count=cnt)) * 1e3
+    if tdt == torch.bfloat16:
+        # what the matrix cores sustain on register operands alone (no LDS, no memory): the
+        # clock the chip holds under MFMA load, next to the published peak
+        mf = {}
+        ms = timed(lambda: mf.__setitem__("flops", zr.debug_mfma_rate(2048, 2048)))
+        aux["mfma_register_only"] = {"TFLOP/s": mf["flops"] / (ms * 1e-3) / 1e12,
+                                     "frac_published_peak": mf["flops"] / (ms * 1e-3) / 1e12 / peak,
+                                     "what": "2048 workgroups x 4 wavefronts x 2048 x 8 independent 32x32x16 bf16 MFMAs, register operands"}
 
     # ---- CPU oracle on the host cores, bounded sample -------------------------
     cpu = None

@@ -275,6 +275,15 @@ const char* zr_debug_last_kernel(void);
  * safe.  Errors: NULL. */
 int zr_debug_time_next_product(void* start_event, void* stop_event);
 
+/* Measuring aid: launches `blocks` workgroups of 4 wavefronts that each issue
+ * `iters` x 8 independent bf16 MFMAs (32 x 32 x 16, fp32 accumulate) on register
+ * operands, with no memory traffic.  Timed by the caller, it gives the rate the
+ * matrix cores sustain at the clock the chip holds under that load, to set beside
+ * the published peak.  sink: device, at least `blocks` floats, overwritten.
+ * Returns the FLOPs the launch performs through *flops (host, may be NULL).
+ * Errors: NULL, SHAPE (blocks or iters < 1, or blocks > 2^20). */
+int zr_debug_mfma_rate(int32_t blocks, int32_t iters, float* sink, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

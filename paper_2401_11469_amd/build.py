@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libzr.so")
-SOURCES = ["zr_api.hip", "zr_select.hip", "zr_impute.hip", "zr_gemm.hip", "zr_gemm_fast.hip", "zr_compact.hip", "zr_priority.hip"]
+SOURCES = ["zr_api.hip", "zr_select.hip", "zr_impute.hip", "zr_gemm.hip", "zr_gemm_fast.hip", "zr_compact.hip", "zr_priority.hip",
+           "zr_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

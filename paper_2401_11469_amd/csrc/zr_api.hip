@@ -140,6 +140,14 @@ int zr_debug_time_next_product(void* start_event, void* stop_event)
     return ZR_OK;
 }
 
+int zr_debug_mfma_rate(int32_t blocks, int32_t iters, float* sink, double* flops, void* stream)
+{
+    if (!sink) return ZR_ERR_NULL;
+    if (blocks < 1 || iters < 1 || blocks > (1 << 20)) return ZR_ERR_SHAPE;
+    if (flops) *flops = mfma_rate_flops(blocks, iters);
+    return launch_mfma_rate(blocks, iters, sink, (hipStream_t)stream);
+}
+
 int zr_extract_kept_columns(const void* in, int64_t ld, int32_t rows, int32_t n,
                             const int32_t* keep_idx, int32_t n_keep,
                             void* out, int64_t ldo, int dtype, void* stream)

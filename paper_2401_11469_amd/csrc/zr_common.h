@@ -108,6 +108,8 @@ int launch_priority_scores(const void* Wt, const void* Wp, int64_t ld, int K, in
                            float* scores, int dtype, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t priority_workspace_bytes(int K, int N, int mode);
 int launch_count_above(const float* scores, int n, float theta, int32_t* count, hipStream_t stream);
+int launch_mfma_rate(int blocks, int iters, float* sink, hipStream_t stream);   // zr_probe.hip
+double mfma_rate_flops(int blocks, int iters);
 int launch_validate(const int32_t* keep_idx, int n_keep, int n, int32_t* flag, hipStream_t stream);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? ZR_OK : ZR_ERR_HIP; }

@@ -71,6 +71,8 @@ _lib.zr_resize_select_multi.argtypes = [_i32, ctypes.POINTER(_vp), ctypes.POINTE
 _lib.zr_resize_select_multi.restype = ctypes.c_int
 _lib.zr_debug_time_next_product.argtypes = [_vp, _vp]
 _lib.zr_debug_time_next_product.restype = ctypes.c_int
+_lib.zr_debug_mfma_rate.argtypes = [_i32, _i32, _vp, ctypes.POINTER(_f64), _vp]
+_lib.zr_debug_mfma_rate.restype = ctypes.c_int
 _lib.zr_validate_keep_idx.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.zr_validate_keep_idx.restype = ctypes.c_int
 
@@ -322,6 +324,14 @@ def debug_time_next_product(start: "torch.cuda.Event", stop: "torch.cuda.Event")
     The events must have been created with enable_timing=True and recorded once
     before (torch creates the HIP event lazily)."""
     _check(_lib.zr_debug_time_next_product(start.cuda_event, stop.cuda_event))
+
+
+def debug_mfma_rate(blocks: int, iters: int, stream=None) -> float:
+    """Launches the register-only MFMA loop (time it with events); returns the FLOPs it performs."""
+    sink = torch.empty(blocks, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    _check(_lib.zr_debug_mfma_rate(blocks, iters, sink.data_ptr(), ctypes.byref(flops), _stream(stream)))
+    return float(flops.value)
 
 
 def debug_last_kernel() -> str:

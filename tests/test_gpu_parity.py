@@ -601,6 +601,15 @@ def test_backward_reuses_what_the_forward_extracted(zr, torch_mod, oracle, polic
         assert np.array_equal(a, b)
 
 
+def test_mfma_rate_probe_runs(zr, torch_mod):
+    """The register-only MFMA loop used as a measuring aid: runs, and reports the FLOPs it does."""
+    flops = zr.debug_mfma_rate(8, 4)
+    torch_mod.cuda.synchronize()
+    assert flops == 8 * 4 * 4 * 8 * 2.0 * 32 * 32 * 16
+    with pytest.raises(zr.ZrError):
+        zr.debug_mfma_rate(0, 4)
+
+
 def test_bitwise_repeatable(zr, torch_mod):
     torch = torch_mod
     case = wl.random_case(5, 300, 520, 390, "bf16")
