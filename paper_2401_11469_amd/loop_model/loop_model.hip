@@ -7,6 +7,7 @@
 //   4   32 MFMAs 32x32x16 per wavefront on register operands
 //   8   the loads of (1) into registers instead (global_load_dwordx4)
 //   64  the reads of (2) requested one MFMA step ahead, as the kernel does
+//   256 with 64 and 4: the MFMAs take the fragments read as their operands, as the kernel does
 // DEPTH = steps of loads in flight; SCHED = where in the step the loads are requested (see load_at).  Nothing is computed with the data; the output is time per
 // step and the core clock (core ticks / 100 MHz wall ticks) seen by one workgroup.
 // Build and run (stand-alone, not part of libzr):
@@ -32,7 +33,8 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
 }
 
 // SCHED 0: every wavefront requests its 8 loads at the top of the step.  SCHED 2: wavefronts 4-7
-// (the SIMD mates of 0-3) request theirs two MFMA steps later.
+// (the SIMD mates of 0-3) request theirs two MFMA steps later.  SCHED 4: wavefronts 0-3 request
+// all 16 loads of a SIMD pair.  SCHED 5: as 0, with the MFMAs issued at raised wave priority.
 template <int MODE, int DEPTH = 1, int SCHED = 0>
 __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B, int ldk, int KT, int tiles_j, float* sink)
 {
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
         pb[q] = B + (size_t)(tj * 256 + row) * ldk + (lane & 7) * 8;
     }
     // zero the LDS once so that the fragment values are finite
-    for (int i = tid; i < 32768; i += 512) smem[i] = 0;
+    for (int i = tid; i < 32768; i += 512) smem[i] = 0x3e003d80u ^ ((uint32_t)i * 0x00010001u & 0x007f007fu);
     __syncthreads();
     const unsigned long long c0 = clock64(), w0 = wall_clock64();
     f32x16 acc[8];
@@ -69,9 +71,18 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
             else dma16(pb[q - 4] + kt * 64, wr + 8192 + (wave + 8 * (q - 4)) * 256);
         };
         const int group = __builtin_amdgcn_readfirstlane(wave >> 2);
-        if ((MODE & 1) && SCHED == 0) {
+        if ((MODE & 1) && (SCHED == 0 || SCHED == 5)) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) load(q);
+        }
+        if ((MODE & 1) && SCHED == 4 && group == 0) {
+            // wavefronts 0-3 request the whole tile (their own rows and their SIMD mates'), 4-7 nothing
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                load(q);
+                if (q < 4) dma16(pa[q] + 32 * (size_t)ldk + kt * 64, wr + (wave + 4 + 8 * q) * 256);
+                else dma16(pb[q - 4] + 32 * (size_t)ldk + kt * 64, wr + 8192 + (wave + 4 + 8 * (q - 4)) * 256);
+            }
         }
         uint4 rg[8];
         if (MODE & 8) {
@@ -92,10 +103,13 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
             }
             if (MODE & 64) {
                 // fragments of the NEXT step requested before this step's MFMAs; the previous
-                // request is consumed first (stands for the MFMAs needing their operands)
+                // request is consumed first (stands for the MFMAs needing their operands), or,
+                // with 256, really is the MFMAs' operands (4 A and 2 B fragments, as in the kernel)
                 const int cb = step & 1, nb = cb ^ 1;
+                if (!(MODE & 256)) {
 #pragma unroll
-                for (int f = 0; f < 6; ++f) { keep.x ^= fr[cb][f].x; keep.y ^= fr[cb][f].y; keep.z ^= fr[cb][f].z; keep.w ^= fr[cb][f].w; }
+                    for (int f = 0; f < 6; ++f) { keep.x ^= fr[cb][f].x; keep.y ^= fr[cb][f].y; keep.z ^= fr[cb][f].z; keep.w ^= fr[cb][f].w; }
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < 6; ++f) fr[nb][f] = *(const uint4*)(rd + ((((step + 1) & 3) * 6 + f) * 64 + lane) * 4);
@@ -109,8 +123,18 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
                 }
             }
             if (MODE & 4) {
+                if (SCHED == 5) __builtin_amdgcn_s_setprio(3);
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[c], 0, 0, 0);
+                for (int c = 0; c < 8; ++c) {
+                    if (MODE & 256) {
+                        union { uint4 u; bf16x8 b; } xa, xb;
+                        xa.u = fr[step & 1][c & 3]; xb.u = fr[step & 1][4 + (c >> 2)];
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa.b, xb.b, acc[c], 0, 0, 0);
+                    } else {
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[c], 0, 0, 0);
+                    }
+                }
+                if (SCHED == 5) __builtin_amdgcn_s_setprio(0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -134,13 +158,24 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
     }
 }
 
+// operands: small bf16 values of both signs (all-zero operands would make the MFMAs draw less power)
+__global__ void fill(uint16_t* p, size_t n)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t h = (uint32_t)(i * 2654435761u) >> 16;
+        // sign, exponent 2^-4 .. 2^-1, 7 mantissa bits
+        p[i] = (uint16_t)(((h & 1u) << 15) | ((123u + ((h >> 1) & 3u)) << 7) | ((h >> 3) & 127u));
+    }
+}
+
 int main(int argc, char** argv)
 {
     const int M = 8192, J = 4096, K = 4096;
     const int ld = K + 64;
     uint16_t *A, *B; float* sink;
     hipMalloc(&A, (size_t)M * ld * 2); hipMalloc(&B, (size_t)J * ld * 2); hipMalloc(&sink, 8192);
-    hipMemset(A, 0, (size_t)M * ld * 2); hipMemset(B, 0, (size_t)J * ld * 2);
+    hipLaunchKernelGGL(fill, dim3(1024), dim3(256), 0, 0, A, (size_t)M * ld);
+    hipLaunchKernelGGL(fill, dim3(1024), dim3(256), 0, 0, B, (size_t)J * ld);
     const int tiles_i = M / 256, tiles_j = J / 256, KT = K / 64;
     const int grid = tiles_i * tiles_j;
     hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
@@ -165,6 +200,9 @@ int main(int argc, char** argv)
     run(mix<6>, "reads+mfma"); run(mix<64 + 4>, "reads ahead+mfma");
     run(mix<5, 1, 2>, "loads staggered+mfma");
     run(mix<7>, "ALL, reads used at once"); run(mix<64 + 5>, "ALL, reads ahead"); run(mix<64 + 5, 1, 2>, "ALL, reads ahead, loads staggered");
+    run(mix<256 + 64 + 4>, "reads ahead feed the mfma"); run(mix<256 + 64 + 5>, "ALL, reads ahead feed the mfma"); run(mix<256 + 64 + 5, 1, 2>, "ALL, reads feed mfma, loads staggered");
+    run(mix<5, 1, 4>, "loads by wavefronts 0-3 only+mfma"); run(mix<256 + 64 + 5, 1, 4>, "ALL, reads feed mfma, loads by wavefronts 0-3");
+    run(mix<5, 1, 5>, "loads+mfma at raised priority"); run(mix<256 + 64 + 5, 1, 5>, "ALL, reads feed mfma, mfma at raised priority");
     hipError_t e = hipDeviceSynchronize();
     printf("status %s\n", hipGetErrorString(e));
     return e == hipSuccess ? 0 : 1;
