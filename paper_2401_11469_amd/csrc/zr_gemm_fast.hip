@@ -28,6 +28,7 @@
 // column in LDS, imputed value first, results on top, 16-byte stores).  Zero and
 // Same imputation happen here; Average leaves per-tile sums for a fill pass.
 #include <cstdio>
+#include <type_traits>
 
 #include "zr_common.h"
 
@@ -45,6 +46,15 @@ constexpr int BK = 64;           // contraction depth of one LDS tile (bf16 elem
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Kernels whose two loaders are direct-to-LDS multiply with 16 x 16 x 32 MFMAs (twice as
+// many instructions of half the size as 32 x 32 x 16): the loads of the next tile get
+// into the instruction stream between them much better (measured on a model of the
+// loop: 13 % less time per step with everything else equal).
+#ifndef ZR_MFMA16
+#define ZR_MFMA16 1
+#endif
 typedef uint16_t E;
 
 // LDS tile layout of the register-staged loaders: 8 blocks (one per group of 8
@@ -508,6 +518,17 @@ struct DmaP {
         {
             return as_frag(*(const uint4*)(stage + off + t * 1024 + (x ^ (step << 3))));
         }
+        // 16 x 16 x 32 operands: lane = row (lane & 15) of sub-tile t, 8 contraction indices
+        // from 8 (lane >> 4) of the 32-deep step: chunk 4 step + (lane >> 4)
+        __device__ __forceinline__ void setup16(int w0, int lane)
+        {
+            off = (w0 + (lane & 15)) * 32;
+            x = (((lane >> 1) & 7) << 2) ^ ((lane >> 4) << 2);
+        }
+        __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int step) const
+        {
+            return as_frag(*(const uint4*)(stage + off + t * 512 + (x ^ (step << 4))));
+        }
     };
 
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int)
@@ -591,6 +612,29 @@ struct DmaQT {
             x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (RP / 2)));
             return x.b;
         }
+        // 16 x 16 x 32 operands: all four 16-lane groups read the sub-tile's 16 columns, group
+        // g = lane >> 4 the contraction rows 8 g .. 8 g + 7 of the 32-deep step (two
+        // transposing reads of 4 rows each).  Up to 8 sub-tiles per wavefront.
+        int rowbase16, coloff16[8];
+        __device__ __forceinline__ void setup16(int w0, int lane)
+        {
+            const int t16 = lane & 15;
+            rowbase16 = (8 * (lane >> 4) + (t16 >> 2)) * (RP / 2);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int col = w0 + t * 16 + 4 * (t16 & 3);
+                coloff16[t] = (((col >> 3) ^ (ZR_QSWZ * (t16 >> 2))) << 2) + ((col & 7) >> 1);
+            }
+        }
+        __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int step) const
+        {
+            typedef __attribute__((address_space(3))) v4i16* lp;
+            const uint32_t* p = stage + 32 * step * (RP / 2) + rowbase16 + coloff16[t];
+            union { v4i16 h[2]; bf16x8 b; } x;
+            x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
+            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (RP / 2)));
+            return x.b;
+        }
     };
 
     __device__ __forceinline__ int tile_row(int q, int tid) const
@@ -656,18 +700,46 @@ constexpr int fast_smem_bytes()
 // and `wr` (the stage being filled) never overlap; declaring that lets the
 // compiler keep the direct-to-LDS loads in flight across the fragment reads
 // instead of waiting for them before the first ds_read.
-template <class LA, class LB, int TM, int TN>
+template <class LA, class LB, int TM, int TN, class ACC>
 __device__ __forceinline__ void pipeline_step(
     LA& la, LB& lb, const typename LA::Reader& ra, const typename LB::Reader& rb,
     const FArgs& g, const uint32_t* __restrict__ rd, uint32_t* __restrict__ wr,
-    int c_next, bool more, int tid, f32x16 (&acc)[TM][TN])
+    int c_next, bool more, int tid, ACC (&acc)[TM][TN])
 {
     constexpr int A_WORDS = LA::WORDS;
+    constexpr bool M16 = sizeof(ACC) == 16;
     if (more) {
         if constexpr (LA::DMA) la.issue(g.A, wr, c_next, g.C, tid); else la.fetch(g.A, c_next, g.C, tid);
         if constexpr (LB::DMA) lb.issue(g.B, wr + A_WORDS, c_next, g.C, tid); else lb.fetch(g.B, c_next, g.C, tid);
     }
-    if constexpr (LA::DMA && LB::DMA) {
+    if constexpr (M16) {
+        // Two 32-deep steps of TM groups (one A fragment against the step's TN B fragments).
+        // The A fragments run through a ring of three, requested two groups ahead; the B
+        // fragments of the second step are requested during the first step's last groups.
+        // So after the first group of a tile no MFMA waits for an LDS round trip, with 44
+        // fragment registers instead of the 96 that two whole steps would take.
+        constexpr int STEPS = BK / 32, G = STEPS * TM;
+        static_assert(TM >= 3, "the ring below is three deep");
+        bf16x8 bfr[2][TN], afr[3];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bfr[0][b] = rb.read16(rd + A_WORDS, b, 0);
+        afr[0] = ra.read16(rd, 0, 0);
+        afr[1] = ra.read16(rd, 1, 0);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const int step = gi / TM;
+            if (gi + 2 < G) afr[(gi + 2) % 3] = ra.read16(rd, (gi + 2) % TM, (gi + 2) / TM);
+            if (step + 1 < STEPS && gi % TM == TM - 3) {
+#pragma unroll
+                for (int b = 0; b < TN; ++b) bfr[(step + 1) & 1][b] = rb.read16(rd + A_WORDS, b, step + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);       // the requests stay above the MFMAs
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                acc[gi % TM][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[gi % 3], bfr[step & 1][b], acc[gi % TM][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if constexpr (LA::DMA && LB::DMA) {
         // No staging registers are live here, so there is room to request the
         // fragments of step s+1 before the MFMAs of step s are issued: the LDS
         // latency hides behind this wavefront's own MFMAs.
@@ -722,9 +794,13 @@ template <template <int, int> class LA_, template <int, int> class LB_, int BM, 
 __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 {
     constexpr int NT = 64 * WM * WN;
-    constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
     typedef LA_<BM, NT> LA;
     typedef LB_<BN, NT> LB;
+    constexpr bool M16 = ZR_MFMA16 && LA::DMA && LB::DMA;
+    constexpr int MT = M16 ? 16 : 32;                  // rows and columns of one MFMA result tile
+    constexpr int AR = M16 ? 4 : 16;                   // accumulator registers per tile and lane
+    constexpr int TM = BM / (MT * WM), TN = BN / (MT * WN);
+    typedef typename std::conditional<M16, f32x4, f32x16>::type ACC;
     constexpr int A_WORDS = LA::WORDS;
     constexpr int B_WORDS = LB::WORDS;
     constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
@@ -744,8 +820,13 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int wc0 = (wave % WN) * (BN / WN);
     typename LA::Reader ra;
     typename LB::Reader rb;
-    ra.setup(wr0, lane);
-    rb.setup(wc0, lane);
+    if constexpr (M16) { ra.setup16(wr0, lane); rb.setup16(wc0, lane); }
+    else { ra.setup(wr0, lane); rb.setup(wc0, lane); }
+    // where this lane's accumulator r of result tile (a, b) lies in the workgroup tile
+    auto acc_row = [&](int a, int r) {
+        return M16 ? wr0 + a * 16 + 4 * (lane >> 4) + r : wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
+    };
+    auto acc_col = [&](int b) { return M16 ? wc0 + b * 16 + (lane & 15) : wc0 + b * 32 + l32; };
 
     // Workgroups go round-robin to the 8 XCDs (each with its own L2): give every
     // XCD a contiguous range of tiles, ordered in groups of 4 tile-rows so that
@@ -789,13 +870,13 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     const int keep_mine = k_list[min(k_first + tid, k_last)];
     const int keep_next = k_list[min(k_first + k_tile, k_last)];
 
-    f32x16 acc[TM][TN];
+    ACC acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+            for (int r = 0; r < AR; ++r) acc[a][b][r] = 0.f;
     if (g.accumulate) {
         // the accumulators start from the old contents of the output (one rounding
         // at the end); done here, where no other registers are live yet
@@ -805,11 +886,11 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 #pragma unroll
             for (int b = 0; b < TN; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
+                for (int r = 0; r < AR; ++r) {
                     // coordinates clamped into the tile instead of a guard: the loads need no
                     // branches and go out together; accumulators outside the tile are never stored
-                    const int row = min(wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3), rows_in_tile - 1);
-                    const int col = min(wc0 + b * 32 + l32, cols_in_tile - 1);
+                    const int row = min(acc_row(a, r), rows_in_tile - 1);
+                    const int col = min(acc_col(b), cols_in_tile - 1);
                     acc[a][b][r] = bf16_bits_to_f32(g.out[(size_t)(i0 + row) * (size_t)g.ldo + j0 + col]);
                 }
     }
@@ -842,7 +923,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
-        pipeline_step<LA, LB, TM, TN>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
+        pipeline_step<LA, LB, TM, TN, ACC>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
                                       (kt + 1) * BK, kt + 1 < KT, tid, acc);
         __syncthreads();
     }
@@ -859,10 +940,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 #pragma unroll
             for (int b = 0; b < TN; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3);
-                    Cs[row * CP + wc0 + b * 32 + l32] = to_bf16(acc[a][b][r]);
-                }
+                for (int r = 0; r < AR; ++r) Cs[acc_row(a, r) * CP + acc_col(b)] = to_bf16(acc[a][b][r]);
     };
 
     if (g.epilogue == EPI_COL_SCATTER) {
@@ -882,7 +960,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         // whole 16-byte stores like a plain tile; only the first and last chunk, which
         // the tile shares with its neighbours, are stored element by element.
         constexpr int HR = BM / 2;
-        static_assert(HR % 32 == 0, "a 32-row MFMA block must lie in one half");
+        static_assert(HR % 32 == 0, "an MFMA result tile must lie in one half");
         constexpr int MAIN_HALFWORDS = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN>() - (BM + BN) * 4) / 2;
         const int a0 = start & ~7;
         const int nchunks = (((end + 7) & ~7) - a0) >> 3;
@@ -892,7 +970,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             int pos[TN];                       // LDS column of this lane's accumulators, -1 beyond the tile
 #pragma unroll
             for (int b = 0; b < TN; ++b) {
-                const int col = wc0 + b * 32 + l32;
+                const int col = acc_col(b);
                 // (clamped into the row: a list that is not ascending must not leave the tile)
                 pos[b] = col < cols_valid ? min(max(idxB[col] - a0, 0), nchunks * 8 - 1) : -1;
             }
@@ -909,15 +987,12 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 __syncthreads();
 #pragma unroll
                 for (int a = 0; a < TM; ++a) {
-                    if ((wr0 + a * 32) / HR != h) continue;
+                    if ((wr0 + a * MT) / HR != h) continue;
 #pragma unroll
                     for (int b = 0; b < TN; ++b) {
                         if (pos[b] < 0) continue;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = wr0 + a * 32 + (r >> 2) * 8 + grp * 4 + (r & 3) - hr0;
-                            Co[row * pitch + pos[b]] = to_bf16(acc[a][b][r]);
-                        }
+                        for (int r = 0; r < AR; ++r) Co[(acc_row(a, r) - hr0) * pitch + pos[b]] = to_bf16(acc[a][b][r]);
                     }
                 }
                 __syncthreads();

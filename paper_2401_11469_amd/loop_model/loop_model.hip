@@ -8,6 +8,7 @@
 //   8   the loads of (1) into registers instead (global_load_dwordx4)
 //   64  the reads of (2) requested one MFMA step ahead, as the kernel does
 //   256 with 64 and 4: the MFMAs take the fragments read as their operands, as the kernel does
+//   512 with 4: twice as many MFMAs of half the size (16x16x32) instead of 32x32x16
 // DEPTH = steps of loads in flight; SCHED = where in the step the loads are requested (see load_at).  Nothing is computed with the data; the output is time per
 // step and the core clock (core ticks / 100 MHz wall ticks) seen by one workgroup.
 // Build and run (stand-alone, not part of libzr):
@@ -20,6 +21,7 @@ typedef __attribute__((address_space(3))) void* lds_void;
 typedef const __attribute__((address_space(1))) void* glb_void;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Direct-to-LDS load written in assembly: the compiler's wait-count pass does not know of it, so
 // every wait in the loop is the one written here (with the builtin it would make each fragment
@@ -58,6 +60,8 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
     const unsigned long long c0 = clock64(), w0 = wall_clock64();
     f32x16 acc[8];
     for (int c = 0; c < 8; ++c) for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+    f32x4 acc4[32];                 // the same 128 accumulator registers as 16 x 16 tiles (MODE & 512)
+    for (int c = 0; c < 32; ++c) for (int r = 0; r < 4; ++r) acc4[c][r] = 0.f;
     bf16x8 fa, fb;
     for (int q = 0; q < 8; ++q) { fa[q] = (__bf16)(0.25f * ((lane + q) % 5)); fb[q] = (__bf16)(0.125f * ((lane * 3 + q) % 7)); }
     uint4 keep = make_uint4(0, 0, 0, 0);
@@ -124,6 +128,20 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
             }
             if (MODE & 4) {
                 if (SCHED == 5) __builtin_amdgcn_s_setprio(3);
+                if (MODE & 512) {
+                    // the same work as 16 MFMAs 16x16x32 (half the size each)
+#pragma unroll
+                    for (int c = 0; c < 16; ++c) {
+                        const int t = (step & 1) * 16 + c;
+                        if (MODE & 256) {
+                            union { uint4 u; bf16x8 b; } xa, xb;
+                            xa.u = fr[step & 1][c & 3]; xb.u = fr[step & 1][4 + ((c >> 2) & 1)];
+                            acc4[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.b, xb.b, acc4[t], 0, 0, 0);
+                        } else {
+                            acc4[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc4[t], 0, 0, 0);
+                        }
+                    }
+                } else
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
                     if (MODE & 256) {
@@ -150,6 +168,7 @@ __global__ __launch_bounds__(512) void mix(const uint16_t* A, const uint16_t* B,
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     float s = 0.f;
     for (int c = 0; c < 8; ++c) for (int r = 0; r < 16; ++r) s += acc[c][r];
+    for (int c = 0; c < 32; ++c) for (int r = 0; r < 4; ++r) s += acc4[c][r];
     if (s == 123.f || keep.x == 0x12345u) sink[blockIdx.x] = s + keep.y + keep.z + keep.w;
     if (blockIdx.x == 17 && tid == 0) {
         const unsigned long long c1 = clock64(), w1 = wall_clock64();
@@ -202,6 +221,7 @@ int main(int argc, char** argv)
     run(mix<7>, "ALL, reads used at once"); run(mix<64 + 5>, "ALL, reads ahead"); run(mix<64 + 5, 1, 2>, "ALL, reads ahead, loads staggered");
     run(mix<256 + 64 + 4>, "reads ahead feed the mfma"); run(mix<256 + 64 + 5>, "ALL, reads ahead feed the mfma"); run(mix<256 + 64 + 5, 1, 2>, "ALL, reads feed mfma, loads staggered");
     run(mix<5, 1, 4>, "loads by wavefronts 0-3 only+mfma"); run(mix<256 + 64 + 5, 1, 4>, "ALL, reads feed mfma, loads by wavefronts 0-3");
+    run(mix<512 + 4>, "mfma 16x16x32"); run(mix<512 + 5>, "loads+mfma 16x16x32"); run(mix<512 + 256 + 64 + 5>, "ALL, reads feed mfma 16x16x32");
     run(mix<5, 1, 5>, "loads+mfma at raised priority"); run(mix<256 + 64 + 5, 1, 5>, "ALL, reads feed mfma, mfma at raised priority");
     hipError_t e = hipDeviceSynchronize();
     printf("status %s\n", hipGetErrorString(e));
