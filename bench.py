@@ -289,10 +289,10 @@ def main() -> int:
         # what the matrix cores sustain on register operands alone (no LDS, no memory): the
         # clock the chip holds under MFMA load, next to the published peak
         mf = {}
-        ms = timed(lambda: mf.__setitem__("flops", zr.debug_mfma_rate(2048, 2048)))
+        ms = timed(lambda: mf.__setitem__("flops", zr.debug_mfma_rate(2048, 512)), n=5)
         aux["mfma_register_only"] = {"TFLOP/s": mf["flops"] / (ms * 1e-3) / 1e12,
                                      "frac_published_peak": mf["flops"] / (ms * 1e-3) / 1e12 / peak,
-                                     "what": "2048 workgroups x 4 wavefronts x 2048 x 8 independent 32x32x16 bf16 MFMAs, register operands"}
+                                     "what": "2048 workgroups x 4 wavefronts x 512 x 8 independent 32x32x16 bf16 MFMAs, register operands"}
 
     # ---- CPU oracle on the host cores, bounded sample -------------------------
     cpu = None

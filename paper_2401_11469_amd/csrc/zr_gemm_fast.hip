@@ -570,6 +570,13 @@ struct DmaP {
 #ifndef ZR_QSWZ
 #define ZR_QSWZ 4
 #endif
+// The 16 x 16 x 32 operand reads take 32 bytes from each of the rows 8 g .. 8 g + 3 per
+// 16-lane group g; groups g and g + 1 are served together, so rows 8 apart must not
+// share banks either: bit 3 of c moves the row by two more chunks (32 bytes).
+#ifndef ZR_QSWZ8
+#define ZR_QSWZ8 2
+#endif
+__device__ __forceinline__ constexpr int q_swizzle(int c) { return (ZR_QSWZ * (c & 3)) ^ (ZR_QSWZ8 * ((c >> 3) & 1)); }
 // MAPPED: the memory rows go through a row list (W[S[c], :]).  A compile-time
 // property, because a run-time "list or identity" choice inside the loop leaves a
 // join whose register copies make the wavefront wait for every outstanding load,
@@ -600,7 +607,7 @@ struct DmaQT {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int col = w0 + t * 32 + 16 * ((lane >> 4) & 1) + 4 * (t16 & 3);
-                coloff[t] = (((col >> 3) ^ (ZR_QSWZ * (t16 >> 2))) << 2) + ((col & 7) >> 1);
+                coloff[t] = (((col >> 3) ^ q_swizzle(8 * (lane >> 5) + (t16 >> 2))) << 2) + ((col & 7) >> 1);
             }
         }
         __device__ __forceinline__ bf16x8 read(const uint32_t* stage, int t, int step) const
@@ -623,7 +630,7 @@ struct DmaQT {
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int col = w0 + t * 16 + 4 * (t16 & 3);
-                coloff16[t] = (((col >> 3) ^ (ZR_QSWZ * (t16 >> 2))) << 2) + ((col & 7) >> 1);
+                coloff16[t] = (((col >> 3) ^ q_swizzle(8 * (lane >> 4) + (t16 >> 2))) << 2) + ((col & 7) >> 1);
             }
         }
         __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int step) const
@@ -653,13 +660,14 @@ struct DmaQT {
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, int*, int C)
     {
         // a lane's LDS slot is fixed; the XOR decides which chunk of the row it fetches.
-        // tile_row(q) & 3 does not depend on q (instructions of one wavefront are a
-        // multiple of 4 rows apart), so neither does the lane being inside the tile
-        static_assert((RPI * NW) % 4 == 0, "rows of successive instructions must agree modulo 4");
-        active_ = (((tid & 63) % CPR) ^ (ZR_QSWZ * (tile_row(0, tid) & 3))) * 8 < R;
+        // The bits of tile_row(q) that enter the swizzle do not depend on q (instructions of
+        // one wavefront are a multiple of 16 rows apart), so neither does the lane being
+        // inside the tile
+        static_assert((RPI * NW) % 16 == 0, "rows of successive instructions must agree modulo 16");
+        active_ = (((tid & 63) % CPR) ^ q_swizzle(tile_row(0, tid))) * 8 < R;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            const int chunk = ((tid & 63) % CPR) ^ (ZR_QSWZ * (tile_row(q, tid) & 3));
+            const int chunk = ((tid & 63) % CPR) ^ q_swizzle(tile_row(q, tid));
             colp[q] = op.base + min(r0 + chunk * 8, op.n_c - 8);     // the readable row length is a multiple of 8
         }
         rows_for(op, 0, C, tid);
@@ -796,7 +804,10 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     constexpr int NT = 64 * WM * WN;
     typedef LA_<BM, NT> LA;
     typedef LB_<BN, NT> LB;
-    constexpr bool M16 = ZR_MFMA16 && LA::DMA && LB::DMA;
+    // (not where both operands come through the transposing reads on a tile larger than
+    // 128 x 128: measured 1-2 % slower there, 10 % faster on the 128 x 128 tiles)
+    constexpr bool both_transposed = LA::NAME[3] == 'Q' && LB::NAME[3] == 'Q';
+    constexpr bool M16 = ZR_MFMA16 && LA::DMA && LB::DMA && !(both_transposed && BM * BN > 128 * 128);
     constexpr int MT = M16 ? 16 : 32;                  // rows and columns of one MFMA result tile
     constexpr int AR = M16 ? 4 : 16;                   // accumulator registers per tile and lane
     constexpr int TM = BM / (MT * WM), TN = BN / (MT * WN);
