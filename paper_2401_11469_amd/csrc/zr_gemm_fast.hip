@@ -663,7 +663,7 @@ struct DmaQT {
         // The bits of tile_row(q) that enter the swizzle do not depend on q (instructions of
         // one wavefront are a multiple of 16 rows apart), so neither does the lane being
         // inside the tile
-        static_assert((RPI * NW) % 16 == 0, "rows of successive instructions must agree modulo 16");
+        static_assert(R == RP || (RPI * NW) % 16 == 0, "rows of successive instructions must agree modulo 16");
         active_ = (((tid & 63) % CPR) ^ q_swizzle(tile_row(0, tid))) * 8 < R;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
