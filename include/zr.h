@@ -14,7 +14,8 @@
  *
  * General conventions
  *  - Every tensor / index pointer is a DEVICE pointer owned by the caller.  The
- *    library allocates nothing, frees nothing and keeps no state between calls.
+ *    library allocates nothing, frees nothing and keeps no state between calls
+ *    (zr_debug.h declares optional measuring aids that do keep a little).
  *  - Tensors are row-major; leading dimensions (ld*) are in ELEMENTS and must be
  *    >= the row length.  bf16 tensors whose base is 16-byte aligned and whose
  *    ld is a multiple of 8 (fp32: 4) take the vectorised paths; anything else is
@@ -22,8 +23,13 @@
  *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*;
  *    NULL = the default stream) and never synchronises, except
  *    zr_validate_keep_idx, which is a debugging aid.
- *  - Errors are return codes; no call aborts or throws.  On any error no kernel
- *    is launched and the outputs are untouched.
+ *  - Errors are return codes; no call aborts or throws.  Every argument check
+ *    happens before the first launch: on NULL, SHAPE, RATIO, INDEX, DTYPE, MODE,
+ *    POLICY and LIMIT nothing is enqueued and the outputs are untouched.  Only
+ *    ZR_ERR_HIP (the runtime refused a launch) can come after earlier kernels of
+ *    the same call were enqueued; the outputs are then undefined.
+ *  - Calls may be made from several host threads (the library keeps no state
+ *    between calls; the aids of zr_debug.h are per thread).
  *  - keep_idx is the kept index set: int32, strictly ascending, unique, within
  *    [0, n) of the pruned axis.  It plays the role of the paper's lineage
  *    tuple: the same list is shared by input and weight (Sec. 3.2) and reused
@@ -86,7 +92,7 @@ typedef enum { ZR_W_KN = 0, ZR_W_NK = 1 } zr_w_layout;
  *  backward call extracts what it needs itself.  Results are identical. */
 typedef enum { ZR_WS_FRESH = 0, ZR_WS_HOLDS_FORWARD = 1 } zr_ws_flags;
 
-/* Imputation policies of Sec. 3.1 ("what value should be imputed"). */
+/* Imputation policies (Sec. 3.1, the paragraph on which value fills a pruned position). */
 typedef enum {
     ZR_IMPUTE_ZERO = 0,     /* +0.0 (the paper's final choice) */
     ZR_IMPUTE_AVERAGE = 1,  /* element-wise mean of the kept slices of this result */
@@ -127,8 +133,8 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
 /* Size of the optional scratch buffer of the forward / backward calls below.
  * With a DEVICE buffer of at least this many bytes (16-byte aligned) the calls
  * first extract the kept columns of the ACTIVATION they would otherwise gather
- * along its contiguous axis (X[:,S] for DROP_K, dY[:,S] for DROP_N; Sec. 3.1:
- * the remaining columns of the input are concatenated) into it,
+ * along its contiguous axis (X[:,S] for DROP_K, dY[:,S] for DROP_N; the pruned
+ * input of Sec. 3.1's forward paragraph) into it,
  * [M x n_keep rounded up to 64] bf16, zero padded, and then run the products on
  * ordinary loads.  The weight shard is never copied or compacted, in either
  * layout.  Without it (NULL, or too small) every gather is done in flight by
@@ -140,8 +146,8 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
  * returns 0 on bad sizes. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
-/* The extraction step on its own (Sec. 3.1: the remaining columns of the input
- * are concatenated in ascending index order): out[r, q] = in[r, keep_idx[q]] for
+/* The extraction step on its own (Sec. 3.1, forward paragraph: the kept columns
+ * of the input, side by side in ascending index order): out[r, q] = in[r, keep_idx[q]] for
  * q < n_keep, and +0 for n_keep <= q < width, width = n_keep rounded up to 64.
  *  in [rows x n] ld, out [rows x width] ldo >= width; bf16 only (else DTYPE);
  *  ld, ldo and n even, in and out 4-byte aligned (else SHAPE).  One launch.
@@ -189,8 +195,8 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
                           const void* prev_dX, const void* prev_dW,
                           void* workspace, size_t workspace_bytes, int workspace_flags, void* stream);
 
-/* Stand-alone recovery/imputation (Sec. 3.1, "Our solution is to add missing
- * dimensions" and the three policies): fills every slice of out[rows x cols]
+/* Stand-alone recovery/imputation (Sec. 3.1, "Consistency Constraint": the
+ * pruned dimensions are put back, and the three policies): fills every slice of out[rows x cols]
  * that is NOT in keep_idx along `axis` (0: keep_idx indexes rows, 1: columns);
  * kept slices are left as they are.
  *  ZERO: +0.0.  SAME: prev[same position] (prev has out's shape and ld; prev ==
@@ -220,6 +226,7 @@ int zr_priority_scores(const void* W_t, const void* W_prev, int64_t ld, int32_t 
                        const float* prev_scores, const int32_t* prev_keep_idx, int32_t n_prev_keep,
                        float* scores, int dtype, void* workspace, size_t workspace_bytes, void* stream);
 size_t zr_priority_workspace_bytes(int32_t K, int32_t N, int mode);
+
 
 /* Eq. 1: pruning ratio gamma = (T_i - T_avg) / M_i from the task's iteration time,
  * the average iteration time and the task's matrix-multiplication time; 0 when
@@ -261,28 +268,6 @@ int zr_migrated_accumulate(const void* A, int64_t lda, const void* B, int64_t ld
  * device int32 used as scratch.  Returns ZR_OK or ZR_ERR_INDEX. */
 int zr_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t n,
                          int32_t* flag, void* stream);
-
-/* Debugging / profiling aid: name (as a profiler prints it, without namespaces) of
- * the GEMM kernel instantiation the last forward / backward call of this
- * process launched.  Not thread safe. */
-const char* zr_debug_last_kernel(void);
-
-/* Profiling aid: the NEXT forward / backward / accumulate product of this process
- * records the two caller-owned HIP events (hipEvent_t, created with timing) on
- * its stream immediately before and after its own GEMM launch(es), leaving out an
- * extraction that precedes it and an imputation pass that follows.  One shot; a
- * backward call that computes dX and dW times the first of the two.  Not thread
- * safe.  Errors: NULL. */
-int zr_debug_time_next_product(void* start_event, void* stop_event);
-
-/* Measuring aid: launches `blocks` workgroups of 4 wavefronts that each issue
- * `iters` x 8 independent bf16 MFMAs (32 x 32 x 16, fp32 accumulate) on register
- * operands, with no memory traffic.  Timed by the caller, it gives the rate the
- * matrix cores sustain at the clock the chip holds under that load, to set beside
- * the published peak.  sink: device, at least `blocks` floats, overwritten.
- * Returns the FLOPs the launch performs through *flops (host, may be NULL).
- * Errors: NULL, SHAPE (blocks or iters < 1, or blocks > 2^20). */
-int zr_debug_mfma_rate(int32_t blocks, int32_t iters, float* sink, double* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -80,21 +80,6 @@ def build(verbose: bool = True, out: str = LIB) -> str:
     return out
 
 
-def build_loop_model(verbose: bool = True) -> str:
-    """Compiles loop_model/loop_model.hip (a stand-alone program: the model of the big tile's main loop)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    src = os.path.join(PKG, "loop_model", "loop_model.hip")
-    out = os.path.join(PKG, "loop_model", "loop_model.bin")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-value",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", src, "-o", out]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return out
-
-
 if __name__ == "__main__":
     build(out=sys.argv[1] if len(sys.argv) > 1 else LIB)
     sys.exit(0)

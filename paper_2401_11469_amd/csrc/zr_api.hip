@@ -8,8 +8,6 @@ using namespace zr;
 
 namespace {
 
-const int64_t kMaxDim = 0x7fffffff;
-
 bool valid_dtype(int dt) { return dt == ZR_F32 || dt == ZR_BF16; }
 bool valid_mode(int m) { return m == ZR_DROP_N || m == ZR_DROP_K; }
 bool valid_policy(int p) { return p == ZR_IMPUTE_ZERO || p == ZR_IMPUTE_AVERAGE || p == ZR_IMPUTE_SAME; }
@@ -130,13 +128,16 @@ const char* zr_status_string(int status)
     }
 }
 
-const char* zr_debug_last_kernel(void) { return g_last_kernel; }
+void zr_debug_record_kernel_names(int on) { g_debug.record_names = on != 0; }
+
+const char* zr_debug_last_kernel(void) { return g_debug.last_kernel; }
 
 int zr_debug_time_next_product(void* start_event, void* stop_event)
 {
     if (!start_event || !stop_event) return ZR_ERR_NULL;
-    g_time_start = (hipEvent_t)start_event;
-    g_time_stop = (hipEvent_t)stop_event;
+    g_debug.start = (hipEvent_t)start_event;
+    g_debug.stop = (hipEvent_t)stop_event;
+    g_debug.armed_once = true;
     return ZR_OK;
 }
 

@@ -4,8 +4,10 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 #include "zr.h"
+#include "zr_debug.h"
 
 namespace zr {
 
@@ -78,8 +80,23 @@ struct GemmDesc {
     int avg_len = 0;
 };
 
-extern char g_last_kernel[128];
-extern hipEvent_t g_time_start, g_time_stop;   // see launch_gemm
+// State of the aids in zr_debug.h, per host thread.  Product calls only test `armed`.
+struct DebugState {
+    bool record_names = false;      // zr_debug_record_kernel_names
+    bool armed_once = false;        // zr_debug_time_next_product: name + events for the next product
+    hipEvent_t start = nullptr, stop = nullptr;
+    char last_kernel[128] = "";
+};
+extern thread_local DebugState g_debug;
+inline bool debug_names_wanted() { return g_debug.record_names || g_debug.armed_once; }
+
+// Dynamic-LDS attribute of a kernel: set once per device and instantiation (the call is
+// idempotent, so two threads racing to set it do no harm; the flags are atomic).
+struct AttrFlags {
+    static constexpr int MAX_DEVICES = 16;
+    std::atomic<bool> done[MAX_DEVICES] = {};
+};
+bool ensure_max_dynamic_lds(const void* fn, int bytes, void* flags16);
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
 int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,

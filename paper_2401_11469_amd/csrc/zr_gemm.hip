@@ -618,14 +618,11 @@ int launch_inst(const KArgs& k, hipStream_t stream)
 {
     constexpr int smem = smem_bytes<BM, BN, DT>();
     auto fn = gemm_kernel<DT, ACC, AVEC, BCC, BVEC, BM, BN>;
-    static bool attr_set = false;   // per instantiation; the attribute is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return ZR_ERR_HIP;
-        attr_set = true;
-    }
-    snprintf(g_last_kernel, sizeof(g_last_kernel), "gemm_kernel<%d, %s, %s, %s, %s, %d, %d>", DT,
-             ACC ? "true" : "false", AVEC ? "true" : "false", BCC ? "true" : "false", BVEC ? "true" : "false", BM, BN);
+    static AttrFlags attr_set;      // per instantiation and device
+    if (!ensure_max_dynamic_lds((const void*)fn, smem, &attr_set)) return ZR_ERR_HIP;
+    if (debug_names_wanted())
+        snprintf(g_debug.last_kernel, sizeof(g_debug.last_kernel), "gemm_kernel<%d, %s, %s, %s, %s, %d, %d>", DT,
+                 ACC ? "true" : "false", AVEC ? "true" : "false", BCC ? "true" : "false", BVEC ? "true" : "false", BM, BN);
     KArgs kk = k;
     kk.tiles_j = (k.J + BN - 1) / BN;
     const int64_t tiles = (int64_t)((k.I + BM - 1) / BM) * kk.tiles_j;
@@ -670,10 +667,21 @@ int launch_dt(const GemmDesc& d, hipStream_t stream)
 
 }  // namespace
 
-// Measurement aid: a pair of events the NEXT product records on its stream right
-// around its own kernel launch(es), i.e. without a preceding extraction or a
-// following imputation pass.  One shot.
-hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+thread_local DebugState g_debug;
+
+bool ensure_max_dynamic_lds(const void* fn, int bytes, void* flags16)
+{
+    AttrFlags* f = (AttrFlags*)flags16;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (dev < 0 || dev >= AttrFlags::MAX_DEVICES) {      // beyond the table: set it every time
+        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+    }
+    if (f->done[dev].load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    f->done[dev].store(true, std::memory_order_release);
+    return true;
+}
 
 static int launch_gemm_untimed(const GemmDesc& d, hipStream_t stream)
 {
@@ -686,11 +694,14 @@ static int launch_gemm_untimed(const GemmDesc& d, hipStream_t stream)
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream)
 {
-    if (!g_time_start) return launch_gemm_untimed(d, stream);
-    hipEvent_t e0 = g_time_start, e1 = g_time_stop;
-    g_time_start = g_time_stop = nullptr;
-    if (hipEventRecord(e0, stream) != hipSuccess) return ZR_ERR_HIP;
+    if (!g_debug.armed_once) return launch_gemm_untimed(d, stream);
+    // measuring aid (zr_debug_time_next_product): events right around this product's own
+    // launch(es), without a preceding extraction or a following imputation pass.  One shot.
+    hipEvent_t e0 = g_debug.start, e1 = g_debug.stop;
+    if (hipEventRecord(e0, stream) != hipSuccess) { g_debug.armed_once = false; return ZR_ERR_HIP; }
     const int st = launch_gemm_untimed(d, stream);
+    g_debug.armed_once = false;
+    g_debug.start = g_debug.stop = nullptr;
     if (hipEventRecord(e1, stream) != hipSuccess) return ZR_ERR_HIP;
     return st;
 }

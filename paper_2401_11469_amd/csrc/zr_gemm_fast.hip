@@ -34,8 +34,6 @@
 
 namespace zr {
 
-char g_last_kernel[128] = "";   // name of the last GEMM kernel launched (debugging aid)
-
 namespace {
 
 constexpr int BK = 64;           // contraction depth of one LDS tile (bf16 elements)
@@ -1200,14 +1198,11 @@ int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
     if (i_end <= i_base || j_end <= j_base) return ZR_OK;
     constexpr int smem = fast_smem_bytes<LA<BM, 64 * WM * WN>::WORDS, LB<BN, 64 * WM * WN>::WORDS, BM, BN>();
     auto fn = fast_kernel<LA, LB, BM, BN, WM, WN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return ZR_ERR_HIP;
-        attr_set = true;
-    }
-    snprintf(g_last_kernel, sizeof(g_last_kernel), "fast_kernel<%s, %s, %d, %d, %d, %d>",
-             LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
+    static AttrFlags attr_set;      // per instantiation and device
+    if (!ensure_max_dynamic_lds((const void*)fn, smem, &attr_set)) return ZR_ERR_HIP;
+    if (debug_names_wanted())
+        snprintf(g_debug.last_kernel, sizeof(g_debug.last_kernel), "fast_kernel<%s, %s, %d, %d, %d, %d>",
+                 LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
     FArgs k = a;
     k.i_base = i_base; k.i_end = i_end; k.j_base = j_base; k.j_end = j_end;
     k.avg_slot_base = slot_base;
@@ -1300,7 +1295,7 @@ int launch_shape(const FArgs& a, hipStream_t stream)
     int st = launch_tile<LA, LB, 256, 256, ZR_BIG_WM, ZR_BIG_WN>(a, 0, sc.big_i_end, 0, sc.big_j_end, stream);
     if (st != ZR_OK || (sc.big_i_end >= a.I && sc.big_j_end >= a.J)) return st;
     char big[128];
-    snprintf(big, sizeof(big), "%s", g_last_kernel);
+    if (debug_names_wanted()) snprintf(big, sizeof(big), "%s", g_debug.last_kernel);
     // Average sums: the remainder panel's tiles continue the slot numbering of the big
     // panel along the summed axis when the cut runs across that axis; panels that
     // cover different output rows (columns) never meet in a slot
@@ -1309,7 +1304,8 @@ int launch_shape(const FArgs& a, hipStream_t stream)
                                                               sums_over_j ? 0 : sc.big_i_end / 256);
     else st = launch_tile<LA, LB, 128, 128, 2, 2>(a, 0, a.I, sc.big_j_end, a.J, stream,
                                                   sums_over_j ? sc.big_j_end / 256 : 0);
-    snprintf(g_last_kernel, sizeof(g_last_kernel), "%.60s + 128x128 remainder panel", big);
+    if (debug_names_wanted())
+        snprintf(g_debug.last_kernel, sizeof(g_debug.last_kernel), "%.60s + 128x128 remainder panel", big);
     return st;
 }
 

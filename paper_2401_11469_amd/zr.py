@@ -49,6 +49,8 @@ _lib.zr_impute.argtypes = [_vp, _i64, _i32, _i32, _i32, _vp, _i32, ctypes.c_int,
 _lib.zr_impute.restype = ctypes.c_int
 _lib.zr_extract_kept_columns.argtypes = [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
 _lib.zr_extract_kept_columns.restype = ctypes.c_int
+_lib.zr_debug_record_kernel_names.argtypes = [ctypes.c_int]
+_lib.zr_debug_record_kernel_names.restype = None
 _lib.zr_debug_last_kernel.argtypes = []
 _lib.zr_debug_last_kernel.restype = ctypes.c_char_p
 _lib.zr_priority_scores.argtypes = [_vp, _vp, _i64, _i32, _i32, ctypes.c_int, _vp, _vp, _i32, _vp, ctypes.c_int,
@@ -332,6 +334,11 @@ def debug_mfma_rate(blocks: int, iters: int, stream=None) -> float:
     flops = ctypes.c_double(0.0)
     _check(_lib.zr_debug_mfma_rate(blocks, iters, sink.data_ptr(), ctypes.byref(flops), _stream(stream)))
     return float(flops.value)
+
+
+def debug_record_kernel_names(on: bool = True) -> None:
+    """Switches the recording of GEMM kernel names on or off for this thread (off by default)."""
+    _lib.zr_debug_record_kernel_names(1 if on else 0)
 
 
 def debug_last_kernel() -> str:

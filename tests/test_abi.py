@@ -11,7 +11,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2401_11469_amd", "libzr.so")
-HEADER = os.path.join(ROOT, "include", "zr.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("zr.h", "zr_debug.h")]
 
 
 @pytest.fixture(scope="module")
@@ -23,7 +23,7 @@ def lib():
 
 
 def _declared_symbols():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(zr_[a-z_0-9]+)\s*\(", text)))
 
@@ -34,7 +34,8 @@ def test_every_declared_symbol_is_exported(lib):
             "zr_impute", "zr_validate_keep_idx", "zr_status_string", "zr_workspace_bytes",
             "zr_extract_kept_columns", "zr_debug_last_kernel", "zr_priority_scores", "zr_pruning_ratio",
             "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes", "zr_migration_range",
-            "zr_migrated_accumulate", "zr_resize_select_multi", "zr_debug_time_next_product"} <= set(names)
+            "zr_migrated_accumulate", "zr_resize_select_multi", "zr_debug_time_next_product",
+            "zr_debug_record_kernel_names", "zr_debug_mfma_rate"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

@@ -19,6 +19,7 @@ def zr():
     import torch
     assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2401_11469_amd import zr as binding
+    binding.debug_record_kernel_names(True)     # tests assert which kernel instantiation ran
     return binding
 
 
@@ -47,9 +48,7 @@ def to_np(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def relf(got, want):
-    den = np.linalg.norm(want)
-    return np.linalg.norm(got - want) / (den if den > 0 else 1.0)
+from parity_util import check_kept_np, relf  # noqa: E402  (tests/ is on sys.path under pytest)
 
 
 def idx_gpu(torch, a):
@@ -219,14 +218,14 @@ def test_migrated_accumulate_parity(zr, torch_mod, oracle, dtype, transposed, M,
     assert torch.all(out._base[:, N:] == 777.0), "padding overwritten"
     want = oracle.migrated_accumulate(base, A[:, begin:end], Wm[:, begin:end] if transposed else Wm[begin:end, :],
                                       transposed)
-    err = np.linalg.norm(to_np(out) - want) / np.linalg.norm(want)
-    assert err <= TOL[dtype], err
-    # a second share lands on top of the first (the receiver may serve several stragglers)
+    first = to_np(out)
+    check_kept_np("out", first, want, dtype, end - begin)
+    # a second share lands on top of the first (the receiver may serve several stragglers):
+    # again one rounding, now of (what the first call stored) + the share
     zr.migrated_accumulate(out, As, Bs, transposed)
-    want2 = oracle.migrated_accumulate(want, A[:, begin:end], Wm[:, begin:end] if transposed else Wm[begin:end, :],
+    want2 = oracle.migrated_accumulate(first, A[:, begin:end], Wm[:, begin:end] if transposed else Wm[begin:end, :],
                                        transposed)
-    err = np.linalg.norm(to_np(out) - want2) / np.linalg.norm(want2)
-    assert err <= 2 * TOL[dtype], err
+    check_kept_np("out, second share", to_np(out), want2, dtype, end - begin)
 
 
 def test_migrated_shares_sum_to_the_stragglers_product(zr, torch_mod, oracle):
@@ -370,14 +369,25 @@ def check_layer(oracle, case, S, mode, dtype, policy, got, tol=None):
     wantdX, wantdW = oracle.resized_linear_bwd(case["X"], case["W"], case["dY"], S, mode, policy,
                                                case.get("prev_dX"), case.get("prev_dW"))
     names = ("Y", "dX", "dW")
-    for name, g, w in zip(names, got, (wantY, wantdX, wantdW)):
+    n = N if mode == DROP_N else K
+    P = np.setdiff1d(np.arange(n), S)
+    kept = np.zeros(n, dtype=bool)
+    kept[S] = True
+    # which positions of each output are products (the rest is imputed), and the length of
+    # the sums behind them
+    if mode == DROP_K:
+        where = (None, kept[None, :], kept[:, None])
+        terms = (len(S), N, M)
+    else:
+        where = (kept[None, :], None, kept[None, :])
+        terms = (K, len(S), M)
+    for name, g, w, wh, C in zip(names, got, (wantY, wantdX, wantdW), where, terms):
         assert g.shape == w.shape
         assert np.all(np.isfinite(g)), name
         e = relf(g, w)
         assert e <= tol, (name, e)
+        check_kept_np(name, g, w, dtype, C, wh)       # element by element at the kept positions
     # imputed positions: bit-exact for Zero / Same
-    n = N if mode == DROP_N else K
-    P = np.setdiff1d(np.arange(n), S)
     if P.size and policy in (ZERO, SAME):
         Y, dX, dW = got
         if mode == DROP_K:
@@ -638,8 +648,9 @@ def test_config1_full(zr, torch_mod, oracle):
     full = np.arange(256, dtype=np.int32)
     got = run_layer(zr, torch, t, full, DROP_N, "f32")
     X, W, dY = (t[k].astype(np.float64) for k in ("X", "W", "dY"))
-    for g, w in zip(got, (X @ W, dY @ W.T, X.T @ dY)):
+    for name, g, w, C in zip(("Y", "dX", "dW"), got, (X @ W, dY @ W.T, X.T @ dY), (512, 256, 256)):
         assert relf(g, w) <= 1e-5
+        check_kept_np(name, g, w, "f32", C)
 
 
 # ------------------------------------------------------ streams and graphs ---
