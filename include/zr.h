@@ -227,6 +227,28 @@ int zr_priority_scores(const void* W_t, const void* W_prev, int64_t ld, int32_t 
                        float* scores, int dtype, void* workspace, size_t workspace_bytes, void* stream);
 size_t zr_priority_workspace_bytes(int32_t K, int32_t N, int mode);
 
+/* zr_priority_scores for callers that cannot allocate or pass scratch memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as zr_priority_scores given a workspace of
+ * zr_priority_workspace_bytes(K, N, mode) bytes (bit for bit: same row ranges,
+ * same summation order), but the per-row-range column sums live in a buffer the
+ * library itself holds in device memory: zr_priority_static_scratch_bytes() =
+ * 1 MiB per GPU, from the moment the library is loaded on that GPU until the
+ * process ends.  The call allocates and frees nothing.  Its first use on a device
+ * looks the buffer's address up (once per device; make that first call outside a
+ * stream capture).
+ *  Limit: zr_priority_workspace_bytes(K, N, mode) <= 1 MiB, else ZR_ERR_LIMIT and
+ *  nothing is enqueued (the row-range split needs about 65536 + N floats, so any N
+ *  up to about 190000 columns fits; ZR_DROP_K needs no scratch at all).
+ *  All calls on one GPU share the buffer, which keeps the last call's contents:
+ *  every slot a call reads it has written itself first, so nothing needs
+ *  clearing, but two calls that overlap on one GPU (different streams, or
+ *  different threads) race on it - order them.
+ *  Errors: NULL, DTYPE, MODE, SHAPE, INDEX, LIMIT, HIP. */
+int zr_priority_scores_static(const void* W_t, const void* W_prev, int64_t ld, int32_t K, int32_t N, int mode,
+                              const float* prev_scores, const int32_t* prev_keep_idx, int32_t n_prev_keep,
+                              float* scores, int dtype, void* stream);
+size_t zr_priority_static_scratch_bytes(void);
 
 /* Eq. 1: pruning ratio gamma = (T_i - T_avg) / M_i from the task's iteration time,
  * the average iteration time and the task's matrix-multiplication time; 0 when

@@ -392,6 +392,25 @@ int zr_priority_scores(const void* W_t, const void* W_prev, int64_t ld, int32_t 
                                   dtype, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+int zr_priority_scores_static(const void* W_t, const void* W_prev, int64_t ld, int32_t K, int32_t N, int mode,
+                              const float* prev_scores, const int32_t* prev_keep_idx, int32_t n_prev_keep,
+                              float* scores, int dtype, void* stream)
+{
+    if (!W_t || !W_prev || !scores) return ZR_ERR_NULL;
+    if (!valid_dtype(dtype)) return ZR_ERR_DTYPE;
+    if (!valid_mode(mode)) return ZR_ERR_MODE;
+    if (K < 1 || N < 1 || ld < N) return ZR_ERR_SHAPE;
+    if (prev_keep_idx) {
+        if (!prev_scores) return ZR_ERR_NULL;
+        const int32_t n = mode == ZR_DROP_N ? N : K;
+        if (n_prev_keep < 1 || n_prev_keep > n) return ZR_ERR_INDEX;
+    }
+    return launch_priority_scores_static(W_t, W_prev, ld, K, N, mode, prev_scores, prev_keep_idx, n_prev_keep,
+                                         scores, dtype, (hipStream_t)stream);
+}
+
+size_t zr_priority_static_scratch_bytes(void) { return priority_static_scratch_bytes(); }
+
 size_t zr_priority_workspace_bytes(int32_t K, int32_t N, int mode)
 {
     if (K < 1 || N < 1 || !valid_mode(mode)) return 0;

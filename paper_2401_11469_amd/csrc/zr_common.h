@@ -124,6 +124,10 @@ int launch_priority_scores(const void* Wt, const void* Wp, int64_t ld, int K, in
                            const float* prev_scores, const int32_t* prev_keep, int n_prev_keep,
                            float* scores, int dtype, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t priority_workspace_bytes(int K, int N, int mode);
+int launch_priority_scores_static(const void* Wt, const void* Wp, int64_t ld, int K, int N, int mode,
+                                  const float* prev_scores, const int32_t* prev_keep, int n_prev_keep,
+                                  float* scores, int dtype, hipStream_t stream);
+size_t priority_static_scratch_bytes();
 int launch_count_above(const float* scores, int n, float theta, int32_t* count, hipStream_t stream);
 int launch_mfma_rate(int blocks, int iters, float* sink, hipStream_t stream);   // zr_probe.hip
 double mfma_rate_flops(int blocks, int iters);

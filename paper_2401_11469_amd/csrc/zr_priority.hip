@@ -5,11 +5,36 @@
 //   L_uni   = #{ i : delta_i > theta }                (differentiated per-layer ratio)
 // HBM-bound reductions over the two weight snapshots; every sum is taken in a
 // fixed order (no floating-point atomics), so results are bitwise repeatable.
+#include <atomic>
+
 #include "zr_common.h"
 
 namespace zr {
 
 namespace {
+
+// Scratch of zr_priority_scores_static: the per-row-range column sums that the ordinary
+// entry point keeps in the caller's workspace.  One copy per GPU the library runs on, held
+// until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels are always given the address that call returned.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 16;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ZR_ERR_HIP;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ZR_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // every thread finds the same address
+    }
+    *out = p;
+    return ZR_OK;
+}
 
 template <typename T, int V> struct Vec;
 template <> struct Vec<float, 1>    { using type = float; };
@@ -260,6 +285,24 @@ int launch_priority_scores(const void* Wt, const void* Wp, int64_t ld, int K, in
                   : rows_typed<uint16_t, 1>(ZR_ARGS(uint16_t), stream);
 #undef ZR_ARGS
 }
+
+int launch_priority_scores_static(const void* Wt, const void* Wp, int64_t ld, int K, int N, int mode,
+                                  const float* prev_scores, const int32_t* prev_keep, int n_prev_keep,
+                                  float* scores, int dtype, hipStream_t stream)
+{
+    if (priority_workspace_bytes(K, N, mode) > kStaticScratchBytes) return ZR_ERR_LIMIT;
+    void* ws = nullptr;
+    if (mode == ZR_DROP_N) {                    // row scores use no scratch
+        const int st = static_scratch(&ws);
+        if (st != ZR_OK) return st;
+    }
+    // every slot of the scratch that the finishing kernel reads is written by the summing
+    // kernel of the same call first: nothing has to be cleared between calls
+    return launch_priority_scores(Wt, Wp, ld, K, N, mode, prev_scores, prev_keep, n_prev_keep, scores, dtype,
+                                  ws, ws ? kStaticScratchBytes : 0, stream);
+}
+
+size_t priority_static_scratch_bytes() { return kStaticScratchBytes; }
 
 int launch_count_above(const float* scores, int n, float theta, int32_t* count, hipStream_t stream)
 {

@@ -58,6 +58,10 @@ _lib.zr_priority_scores.argtypes = [_vp, _vp, _i64, _i32, _i32, ctypes.c_int, _v
 _lib.zr_priority_workspace_bytes.argtypes = [_i32, _i32, ctypes.c_int]
 _lib.zr_priority_workspace_bytes.restype = ctypes.c_size_t
 _lib.zr_priority_scores.restype = ctypes.c_int
+_lib.zr_priority_scores_static.argtypes = [_vp, _vp, _i64, _i32, _i32, ctypes.c_int, _vp, _vp, _i32, _vp, ctypes.c_int, _vp]
+_lib.zr_priority_scores_static.restype = ctypes.c_int
+_lib.zr_priority_static_scratch_bytes.argtypes = []
+_lib.zr_priority_static_scratch_bytes.restype = ctypes.c_size_t
 _lib.zr_pruning_ratio.argtypes = [_f64, _f64, _f64, _f64]
 _lib.zr_pruning_ratio.restype = _f64
 _lib.zr_count_above.argtypes = [_vp, _i32, ctypes.c_float, _vp, _vp]
@@ -280,6 +284,26 @@ def priority_scores(W_t: torch.Tensor, W_prev: torch.Tensor, mode: int,
                                    0 if prev_keep_idx is None else prev_keep_idx.numel(),
                                    scores.data_ptr(), _dtype_code(W_t), *_ws(workspace), _stream(stream)))
     return scores
+
+
+def priority_scores_static(W_t: torch.Tensor, W_prev: torch.Tensor, mode: int, scores: torch.Tensor,
+                           prev_scores: Optional[torch.Tensor] = None, prev_keep_idx: Optional[torch.Tensor] = None,
+                           stream=None) -> torch.Tensor:
+    """zr_priority_scores_static: the library's own scratch, nothing allocated (the caller brings `scores`)."""
+    K, N = W_t.shape
+    (tp, ld), (pp, ldp) = _mat(W_t, "W_t"), _mat(W_prev, "W_prev")
+    if W_prev.shape != W_t.shape or ldp != ld or W_prev.dtype != W_t.dtype:
+        raise ValueError("W_prev must match W_t in shape, leading dimension and dtype")
+    _check(_lib.zr_priority_scores_static(tp, pp, ld, K, N, mode,
+                                          None if prev_scores is None else prev_scores.data_ptr(),
+                                          None if prev_keep_idx is None else prev_keep_idx.data_ptr(),
+                                          0 if prev_keep_idx is None else prev_keep_idx.numel(),
+                                          scores.data_ptr(), _dtype_code(W_t), _stream(stream)))
+    return scores
+
+
+def priority_static_scratch_bytes() -> int:
+    return int(_lib.zr_priority_static_scratch_bytes())
 
 
 def priority_workspace_bytes(K: int, N: int, mode: int) -> int:

@@ -35,7 +35,8 @@ def test_every_declared_symbol_is_exported(lib):
             "zr_extract_kept_columns", "zr_debug_last_kernel", "zr_priority_scores", "zr_pruning_ratio",
             "zr_count_above", "zr_layer_ratio", "zr_priority_workspace_bytes", "zr_migration_range",
             "zr_migrated_accumulate", "zr_resize_select_multi", "zr_debug_time_next_product",
-            "zr_debug_record_kernel_names", "zr_debug_mfma_rate"} <= set(names)
+            "zr_debug_record_kernel_names", "zr_debug_mfma_rate", "zr_priority_scores_static",
+            "zr_priority_static_scratch_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
