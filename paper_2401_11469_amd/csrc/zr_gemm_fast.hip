@@ -28,6 +28,7 @@
 // column in LDS, imputed value first, results on top, 16-byte stores).  Zero and
 // Same imputation happen here; Average leaves per-tile sums for a fill pass.
 #include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 
 #include "zr_common.h"
@@ -199,6 +200,7 @@ __device__ __forceinline__ void interleave4x8(const uint4 r[4], uint2 w[8])
 template <int R, int NT>
 struct LdPV {
     static constexpr const char* NAME = "LdPV";
+    static constexpr bool RING = false;
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -245,6 +247,7 @@ struct LdPV {
 template <int R, int NT>
 struct LdPG {
     static constexpr const char* NAME = "LdPG";
+    static constexpr bool RING = false;
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -306,6 +309,7 @@ struct LdPG {
 template <int R, int NT>
 struct LdQV {
     static constexpr const char* NAME = "LdQV";
+    static constexpr bool RING = false;
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -380,6 +384,7 @@ struct LdQV {
 template <int R, int NT>
 struct LdQG {
     static constexpr const char* NAME = "LdQG";
+    static constexpr bool RING = false;
     typedef Tile<R> T;
     typedef SlotReader<R> Reader;
     static constexpr bool DMA = false;
@@ -497,6 +502,7 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
 template <int R, int NT>
 struct DmaP {
     static constexpr const char* NAME = "DmaP";
+    static constexpr bool RING = false;
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
     static constexpr int WORDS = R * 32;
@@ -582,6 +588,7 @@ __device__ __forceinline__ constexpr int q_swizzle(int c) { return (ZR_QSWZ * (c
 template <int R, int NT, bool MAPPED>
 struct DmaQT {
     static constexpr const char* NAME = MAPPED ? "DmaQM" : "DmaQ";
+    static constexpr bool RING = false;
     static constexpr bool DMA = true;
     static constexpr bool NEEDS_IDX = false;
     static constexpr int RP = R <= 128 ? 128 : 256;
@@ -691,16 +698,262 @@ struct DmaQT {
         }
     }
 };
-template <int R, int NT> using DmaQ = DmaQT<R, NT, false>;
-template <int R, int NT> using DmaQM = DmaQT<R, NT, true>;
+template <int R, int NT> struct DmaQ : DmaQT<R, NT, false> {};
+template <int R, int NT> struct DmaQM : DmaQT<R, NT, true> {};
 
-template <int AW, int BW_, int BM, int BN>
+
+// ---------------------------------------------------------------------------
+// Ring pipeline (direct-to-LDS loaders only).  The contraction runs in stages of
+// 32; four stages of LDS form a ring: while stage s is multiplied, the fragments
+// of stage s+1 are already being read (it became visible at the previous
+// barrier), stage s+2 is landing and stage s+3 is being requested.  What this
+// buys over two 64-deep stages, all of it measured on a model of the loop first:
+//  * every load is requested three stages (> 1 us) before it is needed, so the
+//    requests can be spread over the step, ONE between two MFMAs at a time (a
+//    wavefront stalls at a vector-memory instruction until the address unit takes
+//    it, and the MFMAs queued behind it wait too), and nobody waits for vmcnt(0);
+//  * one fragment read between two MFMAs instead of bursts in front of a group;
+//  * the first fragments of a step are read before the barrier that ends the
+//    previous one, so no MFMA waits for an LDS round trip after a barrier;
+//  * the loads are issued from inline assembly: the compiler's wait-count pass
+//    does not know of them, so its lgkmcnt waits stay exact (with the builtin it
+//    waited for ALL outstanding LDS reads before every MFMA group) and the vmcnt
+//    waits are the ones written here; the LDS address of a load is a scalar and
+//    the global pointers advance by additions (the 64-deep loop spent ~40 vector
+//    ALU instructions per step on addresses, between the barrier and its first MFMA).
+// ---------------------------------------------------------------------------
+constexpr int RK = 32;
+
+__device__ __forceinline__ void dma16_ring(const void* gptr, uint32_t lds_byte_addr_uniform)
+{
+    // m0 = LDS base of the 64 x 16 bytes this instruction writes; no restore: nothing else
+    // in these kernels reads m0
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_byte_addr_uniform) : "memory");
+}
+
+// Contraction axis contiguous (optional row list on the other axis): an LDS row is the
+// 64 bytes (4 chunks) of one tile row; chunk c of row i sits at position c ^ ((i >> 2) & 3),
+// so that the 16 rows a 16-lane group reads together cover all 64 banks.  One instruction
+// brings 16 rows.
+template <int R, int NT>
+struct RingP {
+    static constexpr const char* NAME = "RingP";
+    static constexpr bool RING = true, DMA = true, NEEDS_IDX = false, MAPPED = false;
+    static constexpr int WORDS = R * 16;
+    static constexpr int NW = NT / 64;
+    static constexpr bool FITS = (R / 16) % NW == 0;      // whole instructions per wavefront
+    static constexpr int NI = FITS ? R / 16 / NW : 1;
+    const E* ptr[NI];
+    int chunk_;
+    uint32_t wave_;
+
+    struct Reader {
+        int off;
+        __device__ __forceinline__ void setup16(int w0, int lane)
+        {
+            const int r = lane & 15;
+            off = (w0 + r) * 16 + ((((lane >> 4) ^ (r >> 2)) & 3) << 2);
+        }
+        __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int) const
+        {
+            return as_frag(*(const uint4*)(stage + off + t * 256));
+        }
+    };
+
+    __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, const int*, int)
+    {
+        const int lane = tid & 63;
+        wave_ = __builtin_amdgcn_readfirstlane(tid >> 6);
+        chunk_ = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+        int idx[NI], rows[NI];
+#pragma unroll
+        for (int q = 0; q < NI; ++q) idx[q] = min(r0 + 16 * ((int)wave_ + NW * q) + (lane >> 2), rlim - 1);
+        lookup_rows<NI>(op.map_s, op.n_s, idx, rows);
+#pragma unroll
+        for (int q = 0; q < NI; ++q) ptr[q] = op.base + (size_t)rows[q] * (size_t)op.ld;
+    }
+    __device__ __forceinline__ void issue(const FOp& op, int q, uint32_t lds_bytes, int s, int)
+    {
+        const int c = min(s * RK + chunk_, op.n_c - 8);          // the readable row length is a multiple of 8
+        dma16_ring(ptr[q] + c, lds_bytes + (wave_ + NW * q) * 1024u);
+    }
+};
+
+// Contraction axis strided (optional row list on it, kept in LDS): the LDS stage keeps the 32
+// memory rows as they are, chunk index swizzled as in the 64-deep loader; fragments through
+// the transposing reads.
+template <int R, int NT, bool MAPPED_>
+struct RingQT {
+    static constexpr const char* NAME = MAPPED_ ? "RingQM" : "RingQ";
+    static constexpr bool RING = true, DMA = true, NEEDS_IDX = false, MAPPED = MAPPED_;
+    static constexpr int RP = R <= 128 ? 128 : 256;
+    static constexpr int WORDS = RK * RP / 2;
+    static constexpr int NW = NT / 64;
+    static constexpr int CPR = RP / 8;           // chunk slots per row
+    static constexpr int RPI = 64 / CPR;         // rows per instruction
+    static constexpr bool FITS = (RK / RPI) % NW == 0 && R % 64 == 0 && R > RP / 2;
+    static constexpr int NI = FITS ? RK / RPI / NW : 1;
+    const E* colp;
+    int row_[NI];                                 // row of the stage this lane fetches, per instruction
+    bool active_;
+    uint32_t wave_;
+    const int* list_;                             // LDS copy of the row list (MAPPED)
+
+    struct Reader {
+        int rowbase16, coloff16[8];
+        __device__ __forceinline__ void setup16(int w0, int lane)
+        {
+            const int t16 = lane & 15;
+            rowbase16 = (8 * (lane >> 4) + (t16 >> 2)) * (RP / 2);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int col = w0 + t * 16 + 4 * (t16 & 3);
+                coloff16[t] = (((col >> 3) ^ q_swizzle(8 * (lane >> 4) + (t16 >> 2))) << 2) + ((col & 7) >> 1);
+            }
+        }
+        __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int) const
+        {
+            typedef __attribute__((address_space(3))) v4i16* lp;
+            const uint32_t* p = stage + rowbase16 + coloff16[t];
+            union { v4i16 h[2]; bf16x8 b; } x;
+            x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
+            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * (RP / 2)));
+            return x.b;
+        }
+    };
+
+    __device__ __forceinline__ void init(const FOp& op, int r0, int, int tid, const int* list_lds, int)
+    {
+        const int lane = tid & 63;
+        wave_ = __builtin_amdgcn_readfirstlane(tid >> 6);
+        list_ = list_lds;
+        // the swizzle bits of a lane's row do not depend on the instruction (rows of successive
+        // instructions of a wavefront are 16 apart), so neither does the chunk it fetches
+        static_assert(!FITS || (RPI * NW) % 16 == 0, "rows of successive instructions must agree modulo 16");
+#pragma unroll
+        for (int q = 0; q < NI; ++q) row_[q] = RPI * ((int)wave_ + NW * q) + lane / CPR;
+        const int chunk = (lane % CPR) ^ q_swizzle(row_[0]);
+        active_ = chunk * 8 < R;
+        colp = op.base + min(r0 + chunk * 8, op.n_c - 8);        // the readable row length is a multiple of 8
+    }
+    __device__ __forceinline__ void issue(const FOp& op, int q, uint32_t lds_bytes, int s, int C)
+    {
+        int row = min(s * RK + row_[q], C - 1);
+        if constexpr (MAPPED_) row = list_[row];                  // clamped when it was copied to LDS
+        if (R == RP || active_) dma16_ring(colp + (size_t)row * (size_t)op.ld, lds_bytes + (wave_ + NW * q) * 1024u);
+    }
+};
+template <int R, int NT> struct RingQ : RingQT<R, NT, false> {};
+template <int R, int NT> struct RingQM : RingQT<R, NT, true> {};
+
+// the ring loader that replaces a 64-deep direct-to-LDS loader
+template <template <int, int> class L> struct RingOf { static constexpr bool has = false; };
+template <> struct RingOf<DmaP> { static constexpr bool has = true; template <int R, int NT> using type = RingP<R, NT>; };
+template <> struct RingOf<DmaQ> { static constexpr bool has = true; template <int R, int NT> using type = RingQ<R, NT>; };
+template <> struct RingOf<DmaQM> { static constexpr bool has = true; template <int R, int NT> using type = RingQM<R, NT>; };
+
+// which memory instruction, if any, follows MFMA b of row group gi of a step
+__device__ __forceinline__ constexpr int ring_b_read(int gi, int b, int TM, int TN)
+{
+    if (TN <= TM - 1) return (b == 1 && gi >= TM - 1 - TN && gi < TM - 1) ? gi - (TM - 1 - TN) : -1;
+    // two per group from the first group on
+    if (b == 1) return 2 * gi < TN ? 2 * gi : -1;
+    if (b == 3) return 2 * gi + 1 < TN ? 2 * gi + 1 : -1;
+    return -1;
+}
+__device__ __forceinline__ constexpr int ring_load(int gi, int b, int TM, int NLW)
+{
+    if (b != 2) return -1;
+    for (int j = 0; j < NLW; ++j)
+        if ((j * TM) / NLW == gi) return j;
+    return -1;
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// The whole contraction of one tile.  KT2 (even) stages of 32.
+template <class LA, class LB, int TM, int TN>
+__device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Reader& ra, const typename LB::Reader& rb,
+                                          const FArgs& g, uint32_t* smem, int KT2, f32x4 (&acc)[TM][TN])
+{
+    constexpr int A_WORDS = LA::WORDS, STAGE_WORDS = LA::WORDS + LB::WORDS;
+    constexpr int NA = LA::NI, NLW = LA::NI + LB::NI;
+    constexpr int RA = TM % 4 == 0 ? 4 : 3;                 // depth of the ring of A fragments
+    static_assert(TM % RA == 0 && TM >= 4 && TN >= 4 && NLW <= TM, "schedule below does not fit this wavefront tile");
+    static_assert(TN <= TM - 1 || 2 * (TM - 1) >= TN, "not enough slots for the B fragments");
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+    auto load = [&](int s, int j) {
+        const uint32_t base = lds0 + (uint32_t)(s & 3) * (uint32_t)(STAGE_WORDS * 4);
+        if (j < NA) la.issue(g.A, j, base, s, g.C);
+        else lb.issue(g.B, j - NA, base + A_WORDS * 4, s, g.C);
+    };
+    for (int st = 0; st < 3; ++st) {
+        if (st < KT2) {
+#pragma unroll
+            for (int j = 0; j < NLW; ++j) load(st, j);
+        }
+    }
+    if (KT2 > 2) wait_vmcnt<NLW>(); else wait_vmcnt<0>();     // stages 0 and 1 have landed
+    __builtin_amdgcn_s_barrier();
+
+    bf16x8 bfr[2][TN], afr[RA];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) bfr[0][b] = rb.read16(smem + A_WORDS, b, 0);
+    afr[0] = ra.read16(smem, 0, 0);
+    afr[1] = ra.read16(smem, 1, 0);
+
+    auto step = [&](int s, auto parity) {
+        constexpr int P = decltype(parity)::value;
+        const uint32_t* rd = smem + (s & 3) * STAGE_WORDS;
+        const uint32_t* nx = smem + ((s + 1) & 3) * STAGE_WORDS;
+        const bool more = s + 3 < KT2;
+#pragma unroll
+        for (int gi = 0; gi < TM; ++gi) {
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                acc[gi][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[gi % RA], bfr[P][b], acc[gi][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (b == 0) {
+                    // row group gi + 2 of this stage, or of the next one (visible since the last
+                    // barrier; after the last stage this reads stale LDS that nothing uses)
+                    afr[(gi + 2) % RA] = gi + 2 < TM ? ra.read16(rd, gi + 2, 0) : ra.read16(nx, gi + 2 - TM, 0);
+                }
+                const int jb = ring_b_read(gi, b, TM, TN);
+                if (jb >= 0) bfr[P ^ 1][jb] = rb.read16(nx + A_WORDS, jb, 0);
+                const int jl = ring_load(gi, b, TM, NLW);
+                if (jl >= 0 && more) load(s + 3, jl);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // stage s + 2 (requested during step s - 1) has landed when at most this step's requests are out
+        if (more) wait_vmcnt<NLW>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+    };
+    for (int s = 0; s < KT2; s += 2) {
+        step(s, std::integral_constant<int, 0>());
+        step(s + 1, std::integral_constant<int, 1>());
+    }
+}
+
+// LDS of a workgroup: the stages (two of 64 or, for the ring loaders, four of 32) or the C tile
+// of the epilogue, whichever is larger; then one kept-list entry per tile row and column; then,
+// for a ring loader with a row list on the contraction axis, that list.
+template <class LA, class LB> constexpr bool ring_mapped() { return false; }
+template <int AW, int BW_, int BM, int BN, bool RING = false>
 constexpr int fast_smem_bytes()
 {
-    constexpr int stage_bytes = 2 * (AW + BW_) * 4;
+    constexpr int stage_bytes = (RING ? 4 : 2) * (AW + BW_) * 4;
     constexpr int c_bytes = BM * (BN + 8) * 2;
     return (stage_bytes > c_bytes ? stage_bytes : c_bytes) + (BM + BN) * 4;
 }
+// entries of the LDS copy of the row list (what is left of 160 KB, or of 80 KB for the tiles
+// that run two to a compute unit)
+template <int BM, int BN> constexpr int ring_list_max() { return BM * BN > 128 * 128 ? 6144 : 3072; }
 
 // One iteration of the contraction pipeline.  `rd` (the stage being multiplied)
 // and `wr` (the stage being filled) never overlap; declaring that lets the
@@ -804,8 +1057,10 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     typedef LB_<BN, NT> LB;
     // (not where both operands come through the transposing reads on a tile larger than
     // 128 x 128: measured 1-2 % slower there, 10 % faster on the 128 x 128 tiles)
+    constexpr bool RING = LA::RING;
+    static_assert(LA::RING == LB::RING, "ring loaders come in pairs");
     constexpr bool both_transposed = LA::NAME[3] == 'Q' && LB::NAME[3] == 'Q';
-    constexpr bool M16 = ZR_MFMA16 && LA::DMA && LB::DMA && !(both_transposed && BM * BN > 128 * 128);
+    constexpr bool M16 = RING || (ZR_MFMA16 && LA::DMA && LB::DMA && !(both_transposed && BM * BN > 128 * 128));
     constexpr int MT = M16 ? 16 : 32;                  // rows and columns of one MFMA result tile
     constexpr int AR = M16 ? 4 : 16;                   // accumulator registers per tile and lane
     constexpr int TM = BM / (MT * WM), TN = BN / (MT * WN);
@@ -814,11 +1069,12 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     constexpr int B_WORDS = LB::WORDS;
     constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
     constexpr int CP = BN + 8;
-    constexpr int IDX_OFF = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN>() - (BM + BN) * 4) / 4;
+    constexpr int IDX_OFF = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN, RING>() - (BM + BN) * 4) / 4;
 
     extern __shared__ __align__(16) uint32_t smem[];
     int* idxA = (int*)(smem + IDX_OFF);
     int* idxB = idxA + BM;
+    int* row_list = idxB + BN;          // ring loaders with a row list on the contraction axis
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -906,35 +1162,47 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 
     LA la;
     LB lb;
-    la.init(g.A, i0, g.I, tid, idxA, g.C);
-    lb.init(g.B, j0, g.J, tid, idxB, g.C);
+    if constexpr (RING) {
+        if constexpr (LA::MAPPED || LB::MAPPED) {
+            // the row list of the contraction axis, clamped, for the loads of every stage
+            const FOp& lop = LA::MAPPED ? g.A : g.B;
+            for (int c = tid; c < g.C; c += NT) row_list[c] = clamp_idx(lop.map_s[c], lop.n_s);
+            __syncthreads();
+        }
+        la.init(g.A, i0, g.I, tid, row_list, g.C);
+        lb.init(g.B, j0, g.J, tid, row_list, g.C);
+        if constexpr (M16) ring_main<LA, LB, TM, TN>(la, lb, ra, rb, g, smem, 2 * ((g.C + BK - 1) / BK), acc);
+    } else {
+        la.init(g.A, i0, g.I, tid, idxA, g.C);
+        lb.init(g.B, j0, g.J, tid, idxB, g.C);
 
-    // Pipeline over the contraction tiles: while tile k is multiplied out of LDS
-    // stage k&1, tile k+1 travels: direct-to-LDS loaders write it straight into
-    // the other stage, register-staged loaders hold it in registers and write
-    // it at the end of the iteration.
-    const int KT = (g.C + BK - 1) / BK;
-    auto start_tile = [&](int kt, uint32_t* stage) {
-        if constexpr (LA::DMA) la.issue(g.A, stage, kt * BK, g.C, tid); else la.fetch(g.A, kt * BK, g.C, tid);
-        if constexpr (LB::DMA) lb.issue(g.B, stage + A_WORDS, kt * BK, g.C, tid); else lb.fetch(g.B, kt * BK, g.C, tid);
-    };
-    auto finish_tile = [&](uint32_t* stage) {
-        if constexpr (LA::DMA) la.settle(g.A);
-        if constexpr (LB::DMA) lb.settle(g.B);
-        if constexpr (!LA::DMA) la.commit(g.A, stage, tid);
-        if constexpr (!LB::DMA) lb.commit(g.B, stage + A_WORDS, tid);
-        // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
-        if constexpr (LA::DMA || LB::DMA) __builtin_amdgcn_s_waitcnt(0x0f70);
-    };
-    start_tile(0, smem);
-    finish_tile(smem);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        pipeline_step<LA, LB, TM, TN, ACC>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
-                                      (kt + 1) * BK, kt + 1 < KT, tid, acc);
+        // Pipeline over the contraction tiles: while tile k is multiplied out of LDS
+        // stage k&1, tile k+1 travels: direct-to-LDS loaders write it straight into
+        // the other stage, register-staged loaders hold it in registers and write
+        // it at the end of the iteration.
+        const int KT = (g.C + BK - 1) / BK;
+        auto start_tile = [&](int kt, uint32_t* stage) {
+            if constexpr (LA::DMA) la.issue(g.A, stage, kt * BK, g.C, tid); else la.fetch(g.A, kt * BK, g.C, tid);
+            if constexpr (LB::DMA) lb.issue(g.B, stage + A_WORDS, kt * BK, g.C, tid); else lb.fetch(g.B, kt * BK, g.C, tid);
+        };
+        auto finish_tile = [&](uint32_t* stage) {
+            if constexpr (LA::DMA) la.settle(g.A);
+            if constexpr (LB::DMA) lb.settle(g.B);
+            if constexpr (!LA::DMA) la.commit(g.A, stage, tid);
+            if constexpr (!LB::DMA) lb.commit(g.B, stage + A_WORDS, tid);
+            // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
+            if constexpr (LA::DMA || LB::DMA) __builtin_amdgcn_s_waitcnt(0x0f70);
+        };
+        start_tile(0, smem);
+        finish_tile(smem);
         __syncthreads();
+
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            pipeline_step<LA, LB, TM, TN, ACC>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
+                                          (kt + 1) * BK, kt + 1 < KT, tid, acc);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue -------------------------------------------------------------
@@ -970,7 +1238,7 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         // the tile shares with its neighbours, are stored element by element.
         constexpr int HR = BM / 2;
         static_assert(HR % 32 == 0, "an MFMA result tile must lie in one half");
-        constexpr int MAIN_HALFWORDS = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN>() - (BM + BN) * 4) / 2;
+        constexpr int MAIN_HALFWORDS = (fast_smem_bytes<A_WORDS, B_WORDS, BM, BN, RING>() - (BM + BN) * 4) / 2;
         const int a0 = start & ~7;
         const int nchunks = (((end + 7) & ~7) - a0) >> 3;
         const int pitch = nchunks * 8 + 8;
@@ -1193,16 +1461,20 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 // Host side
 // ---------------------------------------------------------------------------
 template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
-int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream, int slot_base = 0)
+int launch_inst(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream, int slot_base)
 {
-    if (i_end <= i_base || j_end <= j_base) return ZR_OK;
-    constexpr int smem = fast_smem_bytes<LA<BM, 64 * WM * WN>::WORDS, LB<BN, 64 * WM * WN>::WORDS, BM, BN>();
+    typedef LA<BM, 64 * WM * WN> A;
+    typedef LB<BN, 64 * WM * WN> B;
+    constexpr bool ring = A::RING;
+    constexpr int list_bytes = [] { if constexpr (ring) return (A::MAPPED || B::MAPPED) ? ring_list_max<BM, BN>() * 4 : 0; else return 0; }();
+    constexpr int smem = fast_smem_bytes<A::WORDS, B::WORDS, BM, BN, ring>() + list_bytes;
+    static_assert(smem <= 160 * 1024, "LDS of a workgroup");
     auto fn = fast_kernel<LA, LB, BM, BN, WM, WN>;
     static AttrFlags attr_set;      // per instantiation and device
     if (!ensure_max_dynamic_lds((const void*)fn, smem, &attr_set)) return ZR_ERR_HIP;
     if (debug_names_wanted())
         snprintf(g_debug.last_kernel, sizeof(g_debug.last_kernel), "fast_kernel<%s, %s, %d, %d, %d, %d>",
-                 LA<BM, 64 * WM * WN>::NAME, LB<BN, 64 * WM * WN>::NAME, BM, BN, WM, WN);
+                 A::NAME, B::NAME, BM, BN, WM, WN);
     FArgs k = a;
     k.i_base = i_base; k.i_end = i_end; k.j_base = j_base; k.j_end = j_end;
     k.avg_slot_base = slot_base;
@@ -1213,6 +1485,47 @@ int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
     if (grid > 0x7fffffff) return ZR_ERR_LIMIT;
     hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(64 * WM * WN), smem, stream, k);
     return hip_status(hipGetLastError());
+}
+
+// ZR_NO_RING in the environment (read once) keeps every product on the 64-deep two-stage loop:
+// an A/B switch for measurements.
+inline bool ring_enabled()
+{
+    static const bool on = getenv("ZR_NO_RING") == nullptr;
+    return on;
+}
+
+template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
+int launch_tile(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream, int slot_base = 0)
+{
+    if (i_end <= i_base || j_end <= j_base) return ZR_OK;
+    if constexpr (RingOf<LA>::has && RingOf<LB>::has) {
+        constexpr int NT = 64 * WM * WN;
+        typedef typename RingOf<LA>::template type<BM, NT> RA;
+        typedef typename RingOf<LB>::template type<BN, NT> RB;
+        constexpr int TM = BM / (16 * WM), TN = BN / (16 * WN);
+        constexpr int ring_a = TM % 4 == 0 ? 4 : 3;
+        // the ring schedule needs whole load instructions per wavefront and enough MFMA slots
+        // (and tiles above 128 x 128: the small tiles, four wavefronts and two workgroups to a compute
+        // unit, measured 10-25 % slower with a barrier every 32 instead of every 64)
+        constexpr bool fits = RA::FITS && RB::FITS && TM % ring_a == 0 && TM >= 4 && TN >= 4 && RA::NI + RB::NI <= TM &&
+                              (TN <= TM - 1 || 2 * (TM - 1) >= TN) && BM * BN > 128 * 128;
+        if constexpr (fits) {
+            const bool list_ok = !(RA::MAPPED || RB::MAPPED) || a.C <= ring_list_max<BM, BN>();
+            if (ring_enabled() && list_ok) {
+                // (named directly, so that a profiler prints the loaders' own names)
+                constexpr bool ap = std::is_same<RA, RingP<BM, NT>>::value, aq = std::is_same<RA, RingQ<BM, NT>>::value;
+                constexpr bool bp = std::is_same<RB, RingP<BN, NT>>::value, bq = std::is_same<RB, RingQ<BN, NT>>::value;
+                constexpr bool bm = std::is_same<RB, RingQM<BN, NT>>::value;
+                static_assert((ap && (bp || bq || bm)) || (aq && bq), "loader pair without a ring instantiation");
+                if constexpr (ap && bp) return launch_inst<RingP, RingP, BM, BN, WM, WN>(a, i_base, i_end, j_base, j_end, stream, slot_base);
+                else if constexpr (ap && bq) return launch_inst<RingP, RingQ, BM, BN, WM, WN>(a, i_base, i_end, j_base, j_end, stream, slot_base);
+                else if constexpr (ap && bm) return launch_inst<RingP, RingQM, BM, BN, WM, WN>(a, i_base, i_end, j_base, j_end, stream, slot_base);
+                else return launch_inst<RingQ, RingQ, BM, BN, WM, WN>(a, i_base, i_end, j_base, j_end, stream, slot_base);
+            }
+        }
+    }
+    return launch_inst<LA, LB, BM, BN, WM, WN>(a, i_base, i_end, j_base, j_end, stream, slot_base);
 }
 
 // Tile schedule.  The chip has 256 CUs; a 256 x 256 tile occupies one CU (one

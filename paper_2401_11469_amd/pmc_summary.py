@@ -44,9 +44,13 @@ def load(d: str):
     """{kernel: {counter: [value per dispatch]}}"""
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
-        per = collections.defaultdict(float)        # (dispatch, kernel, counter) -> sum over instances
+        # (dispatch, kernel, counter) -> sum over the counter's instances (SQ, TCC: one per shader
+        # engine / XCD / channel), or their maximum for the GRBM clocks (every XCD counts the same span)
+        per = collections.defaultdict(float)
         for row in csv.DictReader(open(f)):
-            per[(row["Dispatch_Id"], short(row["Kernel_Name"]), row["Counter_Name"])] += float(row["Counter_Value"])
+            key = (row["Dispatch_Id"], short(row["Kernel_Name"]), row["Counter_Name"])
+            v = float(row["Counter_Value"])
+            per[key] = max(per[key], v) if row["Counter_Name"].startswith("GRBM_") else per[key] + v
         for (_, k, c), v in per.items():
             acc[k][c].append(v)
     return acc
@@ -74,7 +78,8 @@ def main(d: str, commit: str) -> None:
               f"Byte counters are scaled by what they read for the calibration copy ({COPY_KIB:.0f} KiB read and written per "
               f"dispatch): FETCH_SIZE x {kf:.3f}, WRITE_SIZE x {kw:.3f}.  Values are means over all dispatches of a kernel in the run "
               "(the GEMM instantiations mix the five projections and the per-step ratios).  MB = 1e6 bytes.", "",
-              "MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES (summed over the SIMDs) / (GRBM_GUI_ACTIVE x 1024 SIMDs): the share of "
+              "MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES (summed over its instances) / (GRBM_GUI_ACTIVE (maximum over the XCDs) x 1024 SIMDs), "
+              "the expression of rocprofv3's own derived metric MfmaUtil: the share of "
               "SIMD-cycles in which the matrix pipe is busy while the kernel runs, idle compute units included.", "",
               "| kernel | dispatches | MFMA util | MFMA MOPS (bf16) / dispatch | LDS bank-conflict cycles / LDS active cycles | "
               "wave cycles waiting on any instruction | VMEM reads issued | TA address-FIFO-full cycles | fetched MB | written MB |",
