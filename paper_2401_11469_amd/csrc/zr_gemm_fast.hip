@@ -491,9 +491,22 @@ struct LdQG {
 // its own tail.
 // ---------------------------------------------------------------------------
 
+// Issued from inline assembly (m0 = LDS base of the instruction's 64 x 16 bytes; nothing else
+// in these kernels reads m0).  With the builtin the compiler's wait-count pass counts the load
+// against the LDS counter as well and then waits for ALL outstanding fragment reads (lgkmcnt(0))
+// before every MFMA group; as it is, its lgkmcnt waits are exact and the vmcnt waits are the
+// explicit ones of the pipeline.
+#ifndef ZR_DMA_ASM
+#define ZR_DMA_ASM 1
+#endif
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t* lds_uniform)
 {
+#if ZR_DMA_ASM
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_uniform);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(l) : "memory");
+#else
     __builtin_amdgcn_global_load_lds((glb_void)gptr, (lds_void)lds_uniform, 16, 0, 0);
+#endif
 }
 
 // Contraction axis contiguous in memory (optional row list): LDS row i (128
@@ -551,7 +564,7 @@ struct DmaP {
     }
     __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
     {
-        const int wave = tid >> 6;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int c = min(c0 + chunk_, op.n_c - 8);              // the readable row length is a multiple of 8
 #pragma unroll
         for (int q = 0; q < N; ++q) dma16(ptr[q] + c, stage + (wave + NW * q) * 256);
@@ -680,7 +693,7 @@ struct DmaQT {
     }
     __device__ __forceinline__ void issue(const FOp& op, uint32_t* stage, int c0, int C, int tid)
     {
-        const int wave = tid >> 6;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         if (R == RP || active_) {
 #pragma unroll
             for (int q = 0; q < N; ++q)
@@ -723,6 +736,12 @@ template <int R, int NT> struct DmaQM : DmaQT<R, NT, true> {};
 //    ALU instructions per step on addresses, between the barrier and its first MFMA).
 // ---------------------------------------------------------------------------
 constexpr int RK = 32;
+#ifndef ZR_RING_PEEL
+#define ZR_RING_PEEL 1
+#endif
+#ifndef ZR_RING_LSLOT
+#define ZR_RING_LSLOT 2
+#endif
 
 __device__ __forceinline__ void dma16_ring(const void* gptr, uint32_t lds_byte_addr_uniform)
 {
@@ -864,7 +883,7 @@ __device__ __forceinline__ constexpr int ring_b_read(int gi, int b, int TM, int 
 }
 __device__ __forceinline__ constexpr int ring_load(int gi, int b, int TM, int NLW)
 {
-    if (b != 2) return -1;
+    if (b != ZR_RING_LSLOT) return -1;
     for (int j = 0; j < NLW; ++j)
         if ((j * TM) / NLW == gi) return j;
     return -1;
@@ -907,11 +926,13 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
     afr[0] = ra.read16(smem, 0, 0);
     afr[1] = ra.read16(smem, 1, 0);
 
-    auto step = [&](int s, auto parity) {
+    // steady: the step is known to have a stage s + 3 to request (no branches around the loads)
+    auto step = [&](int s, auto parity, auto steady) {
         constexpr int P = decltype(parity)::value;
+        constexpr bool STEADY = decltype(steady)::value;
         const uint32_t* rd = smem + (s & 3) * STAGE_WORDS;
         const uint32_t* nx = smem + ((s + 1) & 3) * STAGE_WORDS;
-        const bool more = s + 3 < KT2;
+        const bool more = STEADY || s + 3 < KT2;
 #pragma unroll
         for (int gi = 0; gi < TM; ++gi) {
 #pragma unroll
@@ -934,9 +955,16 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
         if (more) wait_vmcnt<NLW>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
     };
-    for (int s = 0; s < KT2; s += 2) {
-        step(s, std::integral_constant<int, 0>());
-        step(s + 1, std::integral_constant<int, 1>());
+    int s = 0;
+#if ZR_RING_PEEL
+    for (; s + 4 < KT2; s += 2) {
+        step(s, std::integral_constant<int, 0>(), std::true_type());
+        step(s + 1, std::integral_constant<int, 1>(), std::true_type());
+    }
+#endif
+    for (; s < KT2; s += 2) {           // the last stages: nothing left to request
+        step(s, std::integral_constant<int, 0>(), std::false_type());
+        step(s + 1, std::integral_constant<int, 1>(), std::false_type());
     }
 }
 
