@@ -8,6 +8,8 @@ using namespace zr;
 
 namespace {
 
+constexpr size_t kSplitScratchBytes = (size_t)64 << 20;
+
 bool valid_dtype(int dt) { return dt == ZR_F32 || dt == ZR_BF16; }
 bool valid_mode(int m) { return m == ZR_DROP_N || m == ZR_DROP_K; }
 bool valid_policy(int p) { return p == ZR_IMPUTE_ZERO || p == ZR_IMPUTE_AVERAGE || p == ZR_IMPUTE_SAME; }
@@ -75,6 +77,27 @@ float* carve_avg(void* workspace, size_t& bytes, size_t need)
     return (float*)((char*)workspace + off);
 }
 
+// Bytes at the start of the workspace that hold (or may still hold, for a backward call after
+// the forward call of the same step) an extracted activation.
+size_t extraction_bytes(int32_t M, int32_t n, int32_t n_keep, int dtype, const void* workspace, size_t workspace_bytes)
+{
+    if (dtype != ZR_BF16 || !workspace || n_keep == n) return 0;
+    const size_t need = (size_t)M * (size_t)round_up64(n_keep) * 2;
+    return need <= workspace_bytes ? need : 0;
+}
+
+// Scratch of a split contraction: what lies between the extracted activation (the first
+// `used` bytes) and the end of the buffer (after the Average sums were carved off its tail).
+void give_split_scratch(GemmDesc& d, void* workspace, size_t bytes, size_t used)
+{
+    d.split_scratch = nullptr; d.split_scratch_bytes = 0;
+    if (!workspace || (uintptr_t)workspace % 16 != 0) return;
+    const size_t off = (used + 15) & ~(size_t)15;
+    if (bytes <= off + 16) return;
+    d.split_scratch = (char*)workspace + off;
+    d.split_scratch_bytes = bytes - off;
+}
+
 // One product with Average imputation: zero the sums, multiply (the scatter epilogue
 // writes results, +0 and the sums), then mean and fill; or, without room for the
 // sums, multiply and run the stand-alone pass that re-reads the kept slices.
@@ -108,7 +131,9 @@ size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int m
     if (M < 1 || K < 1 || N < 1 || n_keep < 1) return 0;
     // extracted activation columns [M x width] (bf16 only), then the per-tile sums of Average imputation
     const size_t act = dtype == ZR_BF16 ? (size_t)M * (size_t)round_up64(n_keep) * 2 : 0;
-    return act + avg_bytes(std::max(M, std::max(K, N)), n_keep) + 16;
+    // + room for the slices of a split contraction (bf16 products with too few tiles for the chip)
+    const size_t split = dtype == ZR_BF16 ? kSplitScratchBytes : 0;
+    return act + 16 + split + avg_bytes(std::max(M, std::max(K, N)), n_keep) + 16;
 }
 
 const char* zr_status_string(int status)
@@ -263,12 +288,14 @@ int zr_resized_linear_fwd(const void* X, int64_t ldx, const void* W, int64_t ldw
             d.A = operand(X, ldx, true, nullptr, S, M, K);
         }
         d.J = N; d.C = n_keep; d.epilogue = EPI_PLAIN; d.out_full = N;
+        give_split_scratch(d, workspace, workspace_bytes, extraction_bytes(M, K, n_keep, dtype, workspace, workspace_bytes));
         return launch_gemm(d, s);
     }
     // Y[m,S[j]] = sum_k X[m,k] * W[k,S[j]], dropped columns imputed
     d.A = operand(X, ldx, true, nullptr, nullptr, M, K);
     d.J = n_keep; d.C = K; d.epilogue = full ? EPI_PLAIN : EPI_COL_SCATTER; d.out_full = N;
     if (needs_prev) d.prev = prev_Y;            // Same: copied by the scatter epilogue itself
+    give_split_scratch(d, workspace, workspace_bytes, 0);
     if (average) return gemm_with_average(d, sums, Y, ldy, M, N, 1, keep_idx, n_keep, dtype, s);
     return launch_gemm(d, s);
 }
@@ -325,6 +352,10 @@ int zr_resized_linear_bwd(const void* X, int64_t ldx, const void* W, int64_t ldw
     GemmDesc d;
     d.dtype = dtype;
     d.keep_idx = S;
+    // (in DROP_K the start of the buffer may hold the forward call's X[:,S] even when this call
+    // extracts nothing itself)
+    give_split_scratch(d, workspace, workspace_bytes,
+                       extraction_bytes(M, mode == ZR_DROP_K ? K : N, n_keep, dtype, workspace, workspace_bytes));
     if (dX) {
         d.out = dX; d.ldo = lddx; d.I = M;
         d.B = weight_dx(W, ldw, K, N, mode, w_layout, S);

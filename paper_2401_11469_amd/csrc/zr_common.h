@@ -78,6 +78,10 @@ struct GemmDesc {
     // axis.  The buffer holds ceil(extent / 128) slots and must be zero beforehand.
     float* avg_partial = nullptr;
     int avg_len = 0;
+    // Scratch for a split contraction (16-byte aligned; products with too few tiles to fill the
+    // chip cut the contraction into slices and add them up in a second launch); nullptr: never split.
+    void* split_scratch = nullptr;
+    size_t split_scratch_bytes = 0;
 };
 
 // State of the aids in zr_debug.h, per host thread.  Product calls only test `armed`.

@@ -123,6 +123,13 @@ struct FArgs {
     float* avg_partial;     // Average imputation: per-tile sums of the stored results, or nullptr
     int avg_len;            // entries per slot of avg_partial
     int avg_slot_base;      // slot of this launch's first tile along the summed axis
+    // Split contraction (products with too few tiles to fill the chip): phase 1 = every workgroup
+    // multiplies one slice of the contraction of one tile and stores its fp32 accumulators to
+    // `partial`; phase 2 = one workgroup per tile adds the slices in slice order and runs the
+    // epilogue.  split <= 1: the ordinary single launch.
+    float* partial;
+    size_t partial_bytes;       // host side only: room at `partial`
+    int split, phase, kt_per;   // kt_per: 64-deep contraction tiles per slice
     // sub-rectangle of D this launch covers, in elements (multiples of 256 except at
     // the far edges of D) and its tile grid
     int i_base, j_base, i_end, j_end;
@@ -570,6 +577,9 @@ struct DmaP {
         for (int q = 0; q < N; ++q) dma16(ptr[q] + c, stage + (wave + NW * q) * 256);
     }
     __device__ __forceinline__ void settle(const FOp&) {}
+    // start the contraction at c0 instead of 0 (a slice of a split contraction): nothing to do,
+    // issue() takes the offset as it comes
+    __device__ __forceinline__ void seek(const FOp&, int, int, int) {}
 };
 
 // Contraction axis strided in memory (optional row list on it): LDS keeps the
@@ -701,6 +711,12 @@ struct DmaQT {
         }
         rows_for(op, c0 + BK, C, tid);
     }
+    // start the contraction at c0 instead of 0 (a slice of a split contraction)
+    __device__ __forceinline__ void seek(const FOp& op, int c0, int C, int tid)
+    {
+        rows_for(op, c0, C, tid);
+        settle(op);
+    }
     // Called after the MFMAs of the step: the row-list entries requested by issue() have
     // long arrived; clamping them here costs no wait and no time before the next issue.
     __device__ __forceinline__ void settle(const FOp& op)
@@ -761,8 +777,12 @@ struct RingP {
     static constexpr bool RING = true, DMA = true, NEEDS_IDX = false, MAPPED = false;
     static constexpr int WORDS = R * 16;
     static constexpr int NW = NT / 64;
-    static constexpr bool FITS = (R / 16) % NW == 0;      // whole instructions per wavefront
-    static constexpr int NI = FITS ? R / 16 / NW : 1;
+    static constexpr int NINST = R / 16;                    // instructions per stage
+    // whole instructions per wavefront, or (192 rows on 8 wavefronts) half of the wavefronts
+    // with one more than the others
+    static constexpr bool FITS = NINST % NW == 0 || NINST % NW == NW / 2;
+    static constexpr int NI = (NINST + NW - 1) / NW;
+    static constexpr int SHORT = NINST % NW == 0 ? 0 : 1;   // instructions the higher wavefronts leave out
     const E* ptr[NI];
     int chunk_;
     uint32_t wave_;
@@ -780,6 +800,9 @@ struct RingP {
         }
     };
 
+    // how many of its NI instructions this wavefront issues per stage
+    __device__ __forceinline__ int count() const { return SHORT && wave_ >= (uint32_t)(NINST % NW) ? NI - 1 : NI; }
+
     __device__ __forceinline__ void init(const FOp& op, int r0, int rlim, int tid, const int*, int)
     {
         const int lane = tid & 63;
@@ -794,6 +817,7 @@ struct RingP {
     }
     __device__ __forceinline__ void issue(const FOp& op, int q, uint32_t lds_bytes, int s, int)
     {
+        if (SHORT && q == NI - 1 && wave_ >= (uint32_t)(NINST % NW)) return;      // uniform
         const int c = min(s * RK + chunk_, op.n_c - 8);          // the readable row length is a multiple of 8
         dma16_ring(ptr[q] + c, lds_bytes + (wave_ + NW * q) * 1024u);
     }
@@ -813,6 +837,8 @@ struct RingQT {
     static constexpr int RPI = 64 / CPR;         // rows per instruction
     static constexpr bool FITS = (RK / RPI) % NW == 0 && R % 64 == 0 && R > RP / 2;
     static constexpr int NI = FITS ? RK / RPI / NW : 1;
+    static constexpr int SHORT = 0;
+    __device__ __forceinline__ int count() const { return NI; }
     const E* colp;
     int row_[NI];                                 // row of the stage this lane fetches, per instruction
     bool active_;
@@ -898,8 +924,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // The whole contraction of one tile.  KT2 (even) stages of 32.
 template <class LA, class LB, int TM, int TN>
 __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Reader& ra, const typename LB::Reader& rb,
-                                          const FArgs& g, uint32_t* smem, int KT2, f32x4 (&acc)[TM][TN])
+                                          const FArgs& g, uint32_t* smem, int s0, int KT2, f32x4 (&acc)[TM][TN])
 {
+    // s0: first stage (of 32) of this workgroup's share of the contraction; LDS slots go by the
+    // stage's number within the share, addresses by its absolute number
     constexpr int A_WORDS = LA::WORDS, STAGE_WORDS = LA::WORDS + LB::WORDS;
     constexpr int NA = LA::NI, NLW = LA::NI + LB::NI;
     constexpr int RA = TM % 4 == 0 ? 4 : 3;                 // depth of the ring of A fragments
@@ -908,8 +936,8 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     auto load = [&](int s, int j) {
         const uint32_t base = lds0 + (uint32_t)(s & 3) * (uint32_t)(STAGE_WORDS * 4);
-        if (j < NA) la.issue(g.A, j, base, s, g.C);
-        else lb.issue(g.B, j - NA, base + A_WORDS * 4, s, g.C);
+        if (j < NA) la.issue(g.A, j, base, s0 + s, g.C);
+        else lb.issue(g.B, j - NA, base + A_WORDS * 4, s0 + s, g.C);
     };
     for (int st = 0; st < 3; ++st) {
         if (st < KT2) {
@@ -917,7 +945,16 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
             for (int j = 0; j < NLW; ++j) load(st, j);
         }
     }
-    if (KT2 > 2) wait_vmcnt<NLW>(); else wait_vmcnt<0>();     // stages 0 and 1 have landed
+    // a wavefront waits until at most ITS requests of one stage are outstanding (a loader whose
+    // instructions do not divide over the wavefronts leaves some with one fewer)
+    const int mine = la.count() + lb.count();
+    auto wait_one_stage = [&] {
+        if constexpr (LA::SHORT + LB::SHORT == 0) wait_vmcnt<NLW>();
+        else if (mine == NLW) wait_vmcnt<NLW>();
+        else if (mine == NLW - 1) wait_vmcnt<NLW - 1>();
+        else wait_vmcnt<(NLW >= 2 ? NLW - 2 : 0)>();
+    };
+    if (KT2 > 2) wait_one_stage(); else wait_vmcnt<0>();      // stages 0 and 1 have landed
     __builtin_amdgcn_s_barrier();
 
     bf16x8 bfr[2][TN], afr[RA];
@@ -952,7 +989,7 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
             }
         }
         // stage s + 2 (requested during step s - 1) has landed when at most this step's requests are out
-        if (more) wait_vmcnt<NLW>(); else wait_vmcnt<0>();
+        if (more) wait_one_stage(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
     };
     int s = 0;
@@ -1077,7 +1114,10 @@ __device__ __forceinline__ void pipeline_step(
     }
 }
 
-template <template <int, int> class LA_, template <int, int> class LB_, int BM, int BN, int WM, int WN>
+// PHASE: 0 = the whole product in one launch; 1 / 2 = the two launches of a split contraction
+// (instantiated for the 128 x 128 direct-to-LDS tiles only: separate kernels, so that the
+// ordinary one keeps its register allocation).
+template <template <int, int> class LA_, template <int, int> class LB_, int BM, int BN, int WM, int WN, int PHASE = 0>
 __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 {
     constexpr int NT = 64 * WM * WN;
@@ -1126,9 +1166,13 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
     // the tiles running together share A rows and B columns.
     const int nb = gridDim.x;                  // a multiple of 8 (the host pads the grid)
     const int per = nb / 8;
-    const int t = (blockIdx.x % 8) * per + blockIdx.x / 8;
+    const int lin = (blockIdx.x % 8) * per + blockIdx.x / 8;
     const int total = g.tiles_i * g.tiles_j;
-    if (t >= total) return;
+    // phase 1 of a split contraction: slice z of tile t; all tiles of a slice are neighbours in
+    // the launch order, so they still sweep the same contraction range together
+    const int z = PHASE == 1 ? lin / total : 0;
+    const int t = PHASE == 1 ? lin - z * total : lin;
+    if (lin >= total * (PHASE == 1 ? g.split : 1)) return;
     constexpr int GI = 4;
     const int grp_sz = GI * g.tiles_j;
     const int gidx = t / grp_sz;
@@ -1188,9 +1232,44 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
                 }
     }
 
+    // this workgroup's share of the contraction, in 64-deep tiles
+    const int KT_all = (g.C + BK - 1) / BK;
+    const int kt0 = PHASE == 1 ? z * g.kt_per : 0;
+    const int kt1 = PHASE == 1 ? min(kt0 + g.kt_per, KT_all) : KT_all;
+    // accumulator sub-tiles (a, b) of this wavefront that hold anything of the output: the
+    // slices of a split contraction are only exchanged for those
+    auto sub_valid = [&](int a, int b) {
+        return wr0 + a * MT < min(BM, g.I - i0) && wc0 + b * MT < min(BN, g.J - j0);
+    };
+    float4* part = nullptr;
+    if constexpr (M16 && PHASE != 0)
+        part = (float4*)g.partial + ((size_t)z * (size_t)total + (size_t)t) * (size_t)(TM * TN * NT) + tid;
+
     LA la;
     LB lb;
-    if constexpr (RING) {
+    if constexpr (PHASE == 2) {
+        // the slices in slice order (a fixed order: results are repeatable bit by bit)
+        if constexpr (M16) {
+            // all slices of a sub-tile are requested together (one memory latency per sub-tile,
+            // not one per slice) and added in slice order; split <= 8
+            const size_t zstride = (size_t)total * (size_t)(TM * TN * NT);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    if (sub_valid(a, b)) {
+                        float4 v[8];
+#pragma unroll
+                        for (int zz = 0; zz < 8; ++zz)
+                            v[zz] = part[(size_t)min(zz, g.split - 1) * zstride + (a * TN + b) * NT];
+#pragma unroll
+                        for (int zz = 0; zz < 8; ++zz)
+                            if (zz < g.split) {
+                                acc[a][b][0] += v[zz].x; acc[a][b][1] += v[zz].y; acc[a][b][2] += v[zz].z; acc[a][b][3] += v[zz].w;
+                            }
+                    }
+        }
+    } else if constexpr (RING) {
         if constexpr (LA::MAPPED || LB::MAPPED) {
             // the row list of the contraction axis, clamped, for the loads of every stage
             const FOp& lop = LA::MAPPED ? g.A : g.B;
@@ -1199,16 +1278,18 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
         }
         la.init(g.A, i0, g.I, tid, row_list, g.C);
         lb.init(g.B, j0, g.J, tid, row_list, g.C);
-        if constexpr (M16) ring_main<LA, LB, TM, TN>(la, lb, ra, rb, g, smem, 2 * ((g.C + BK - 1) / BK), acc);
+        if constexpr (M16) ring_main<LA, LB, TM, TN>(la, lb, ra, rb, g, smem, 2 * kt0, 2 * (kt1 - kt0), acc);
     } else {
         la.init(g.A, i0, g.I, tid, idxA, g.C);
         lb.init(g.B, j0, g.J, tid, idxB, g.C);
+        if constexpr (LA::DMA && LB::DMA) {      // (the host only splits products of these loaders)
+            if (kt0 > 0) { la.seek(g.A, kt0 * BK, g.C, tid); lb.seek(g.B, kt0 * BK, g.C, tid); }
+        }
 
-        // Pipeline over the contraction tiles: while tile k is multiplied out of LDS
-        // stage k&1, tile k+1 travels: direct-to-LDS loaders write it straight into
+        // Pipeline over the contraction tiles: while tile k is multiplied out of one LDS
+        // stage, tile k+1 travels: direct-to-LDS loaders write it straight into
         // the other stage, register-staged loaders hold it in registers and write
         // it at the end of the iteration.
-        const int KT = (g.C + BK - 1) / BK;
         auto start_tile = [&](int kt, uint32_t* stage) {
             if constexpr (LA::DMA) la.issue(g.A, stage, kt * BK, g.C, tid); else la.fetch(g.A, kt * BK, g.C, tid);
             if constexpr (LB::DMA) lb.issue(g.B, stage + A_WORDS, kt * BK, g.C, tid); else lb.fetch(g.B, kt * BK, g.C, tid);
@@ -1221,16 +1302,29 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
             // direct-to-LDS loads are only tracked by the vector-memory counter: vmcnt(0)
             if constexpr (LA::DMA || LB::DMA) __builtin_amdgcn_s_waitcnt(0x0f70);
         };
-        start_tile(0, smem);
+        start_tile(kt0, smem);
         finish_tile(smem);
         __syncthreads();
 
-        for (int kt = 0; kt < KT; ++kt) {
-            const int cur = kt & 1;
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int cur = (kt - kt0) & 1;
             pipeline_step<LA, LB, TM, TN, ACC>(la, lb, ra, rb, g, smem + cur * STAGE_WORDS, smem + (cur ^ 1) * STAGE_WORDS,
-                                          (kt + 1) * BK, kt + 1 < KT, tid, acc);
+                                          (kt + 1) * BK, kt + 1 < kt1, tid, acc);
             __syncthreads();
         }
+    }
+
+    if constexpr (PHASE == 1) {
+        // this slice's accumulators, as they are; phase 2 adds the slices and stores the output
+        if constexpr (M16) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    if (sub_valid(a, b))
+                        part[(a * TN + b) * NT] = make_float4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+        }
+        return;
     }
 
     // ---- epilogue -------------------------------------------------------------
@@ -1488,6 +1582,13 @@ __global__ __launch_bounds__(64 * WM * WN) void fast_kernel(const FArgs g)
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
+// ZR_NO_SPLIT in the environment (read once) switches the split contraction off: an A/B switch.
+inline bool split_enabled()
+{
+    static const bool on = getenv("ZR_NO_SPLIT") == nullptr;
+    return on;
+}
+
 template <template <int, int> class LA, template <int, int> class LB, int BM, int BN, int WM, int WN>
 int launch_inst(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hipStream_t stream, int slot_base)
 {
@@ -1509,8 +1610,43 @@ int launch_inst(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
     k.tiles_i = (i_end - i_base + BM - 1) / BM;
     k.tiles_j = (j_end - j_base + BN - 1) / BN;
     const int64_t tiles = (int64_t)k.tiles_i * k.tiles_j;
+    if (tiles > 0x7ffffff0) return ZR_ERR_LIMIT;
+    k.phase = 0; k.split = 1; k.kt_per = 0;
+    // Split contraction: when this launch has too few tiles for the chip and a long contraction,
+    // s slices per tile (s * tiles workgroups), then one more launch of the same kernel that adds
+    // the slices and runs the epilogue.  Needs scratch for the slices (the caller's workspace).
+    constexpr bool can_split = A::DMA && B::DMA && !ring && BM == 128 && BN == 128;
+    if constexpr (can_split) {
+        const int KT = (a.C + BK - 1) / BK;
+        const int64_t slots = (BM * BN > 128 * 128) ? 256 : 512;          // workgroups the chip holds at once
+        int sp = (int)std::min<int64_t>(slots / tiles, 8);
+        sp = std::min(sp, KT / 8);                                         // at least 8 contraction tiles (512 deep) per slice
+        const size_t per_slice = (size_t)tiles * (size_t)BM * (size_t)BN * 4;
+        if (a.partial && per_slice > 0) sp = (int)std::min<size_t>((size_t)std::max(sp, 0), a.partial_bytes / per_slice);
+        else sp = 1;
+        if (sp >= 2 && !a.accumulate && split_enabled()) {
+            k.split = sp; k.kt_per = (KT + sp - 1) / sp;
+            k.split = (KT + k.kt_per - 1) / k.kt_per;                      // no empty slice
+            auto fn1 = fast_kernel<LA, LB, BM, BN, WM, WN, 1>;
+            auto fn2 = fast_kernel<LA, LB, BM, BN, WM, WN, 2>;
+            static AttrFlags attr1, attr2;
+            if (!ensure_max_dynamic_lds((const void*)fn1, smem, &attr1) || !ensure_max_dynamic_lds((const void*)fn2, smem, &attr2))
+                return ZR_ERR_HIP;
+            k.phase = 1;
+            const int64_t g1 = (tiles * k.split + 7) / 8 * 8;
+            hipLaunchKernelGGL(fn1, dim3((unsigned)g1), dim3(64 * WM * WN), smem, stream, k);
+            if (hipGetLastError() != hipSuccess) return ZR_ERR_HIP;
+            k.phase = 2;
+            hipLaunchKernelGGL(fn2, dim3((unsigned)((tiles + 7) / 8 * 8)), dim3(64 * WM * WN), smem, stream, k);
+            if (debug_names_wanted()) {
+                char nm[128];
+                snprintf(nm, sizeof(nm), "%.90s split %d", g_debug.last_kernel, k.split);
+                snprintf(g_debug.last_kernel, sizeof(g_debug.last_kernel), "%s", nm);
+            }
+            return hip_status(hipGetLastError());
+        }
+    }
     const int64_t grid = (tiles + 7) / 8 * 8;
-    if (grid > 0x7fffffff) return ZR_ERR_LIMIT;
     hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(64 * WM * WN), smem, stream, k);
     return hip_status(hipGetLastError());
 }
@@ -1682,6 +1818,8 @@ int launch_gemm_fast(const GemmDesc& d, hipStream_t stream)
     a.avg_partial = d.epilogue == EPI_PLAIN ? nullptr : d.avg_partial; a.avg_len = d.avg_len; a.avg_slot_base = 0;
     a.tiles_i = a.tiles_j = 0;
     a.i_base = a.j_base = a.i_end = a.j_end = 0;
+    a.partial = (float*)d.split_scratch; a.partial_bytes = d.split_scratch ? d.split_scratch_bytes : 0;
+    a.split = 1; a.phase = 0; a.kt_per = 0;
     const bool ag = d.A.map_contig != nullptr, bg = d.B.map_contig != nullptr;
     // Direct-to-LDS loaders cannot zero the contraction tail of the last tile
     // themselves: either the tiles are full, or one operand supplies the zeros

@@ -36,7 +36,10 @@ N_SIMD = 256 * 4
 def short(k: str) -> str:
     k = k.replace("zr::(anonymous namespace)::", "").replace("void ", "")
     if ">(" in k and "_kernel<" in k:
-        return k[:k.index(">(") + 1]
+        k = k[:k.index(">(") + 1]
+        # the trailing phase parameter of the GEMM kernels: 0 (the ordinary launch) is left out,
+        # as in the names the library itself reports
+        return k[:-4] + ">" if k.startswith("fast_kernel<") and k.endswith(", 0>") else k
     return k.split("(")[0]
 
 

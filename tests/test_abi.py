@@ -59,9 +59,10 @@ def test_workspace_bytes_host_function(lib):
     f.restype = ctypes.c_size_t
     def sums(length, n_keep):            # per-tile sums of Average imputation: ceil(n_keep/128) slots of fp32
         return ((n_keep + 127) // 128 * length * 4 + 15) // 16 * 16 + 16
-    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2 + sums(8192, 2304)   # dY[:,S]; 2304 = 36 * 64
-    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2 + sums(8192, 2064)   # X[:,S]; 2064 -> 2112
-    assert f(256, 512, 256, 192, 0, 0) == sums(512, 192)                           # fp32: no extraction
+    split = 16 + (64 << 20)              # bf16: room for the slices of a split contraction
+    assert f(8192, 4096, 3072, 2304, 0, 1) == 8192 * 2304 * 2 + split + sums(8192, 2304)   # dY[:,S]; 2304 = 36 * 64
+    assert f(8192, 2752, 4096, 2064, 1, 1) == 8192 * 2112 * 2 + split + sums(8192, 2064)   # X[:,S]; 2064 -> 2112
+    assert f(256, 512, 256, 192, 0, 0) == 16 + sums(512, 192)                      # fp32: no extraction, no split
     assert f(0, 8, 8, 4, 0, 1) == 0
 
 

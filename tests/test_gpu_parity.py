@@ -588,6 +588,39 @@ def test_workspace_path_matches_oracle_and_in_flight_path(zr, torch_mod, oracle,
         check_layer(oracle, case, S, mode, "bf16", policy, got)
 
 
+@pytest.mark.parametrize("mode", [DROP_N, DROP_K])
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (264, 1536, 2056), (2100, 1100, 136)])
+def test_split_contraction_parity(zr, torch_mod, oracle, mode, M, K, N):
+    """Few output tiles and a long contraction: with the scratch buffer the contraction is cut into
+    slices that a second launch adds up (fp32, fixed order).  Against the oracle element by element,
+    all three policies; repeatable bit by bit; and the path without scratch (never split) agrees to
+    one rounding of the output."""
+    torch = torch_mod
+    case = wl.random_case(77 + M + K + N, M, K, N, "bf16")
+    n = N if mode == DROP_N else K
+    # the forward product in the row-gather layout is one that splits: check that it does
+    nk = mode == DROP_N
+    Sx = subset(9, n, (3 * n) // 4)
+    Xg = to_gpu(torch, case["X"], "bf16")
+    Wg = to_gpu(torch, np.ascontiguousarray(case["W"].T) if nk else case["W"], "bf16")
+    wsx = torch.empty(zr.workspace_bytes(M, K, N, len(Sx), mode, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    zr.resized_linear_fwd(Xg, Wg, idx_gpu(torch, Sx), mode, workspace=wsx, w_layout=W_NK if nk else W_KN)
+    torch.cuda.synchronize()
+    if (K if mode == DROP_N else len(Sx)) >= 1024 and M <= 512:
+        assert "split" in zr.debug_last_kernel(), zr.debug_last_kernel()
+    for layout in (W_KN, W_NK):
+        S = subset(3 * n + layout, n, (3 * n) // 4)
+        for policy in (ZERO, SAME, AVERAGE):
+            a = run_layer(zr, torch, case, S, mode, "bf16", policy, use_ws=True, w_layout=layout)
+            check_layer(oracle, case, S, mode, "bf16", policy, a)
+        a = run_layer(zr, torch, case, S, mode, "bf16", use_ws=True, w_layout=layout)
+        a2 = run_layer(zr, torch, case, S, mode, "bf16", use_ws=True, w_layout=layout)
+        b = run_layer(zr, torch, case, S, mode, "bf16", use_ws=False, w_layout=layout)
+        for x, x2, y in zip(a, a2, b):
+            assert np.array_equal(x, x2)
+            assert np.max(np.abs(x - y)) <= 2.0 ** -7 * np.max(np.abs(y))
+
+
 @pytest.mark.parametrize("policy", [ZERO, AVERAGE])
 def test_backward_reuses_what_the_forward_extracted(zr, torch_mod, oracle, policy):
     """DROP_K: the forward leaves X[:,S] in the scratch buffer; a backward call that is told
