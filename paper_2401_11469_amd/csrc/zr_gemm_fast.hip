@@ -1715,14 +1715,18 @@ inline int64_t tiles_of(int I, int J, int bm, int bn) { return (int64_t)((I + bm
 inline double cost_192(int64_t tiles) { return ZR_COST_192 * (double)((tiles + 255) / 256); }
 
 #ifndef ZR_COST_SMALL1
-#define ZR_COST_SMALL1 0.42
+#define ZR_COST_SMALL1 0.46
 #endif
 #ifndef ZR_COST_SMALL2
-#define ZR_COST_SMALL2 0.70
+#define ZR_COST_SMALL2 0.77
+#endif
+#ifndef ZR_COST_SPLIT
+#define ZR_COST_SPLIT 0.30
 #endif
 inline double small_cost(int64_t ts)
 {
     if (ts <= 0) return 0.0;
+    if (ts <= 128) return ZR_COST_SPLIT;                        // few tiles: the contraction is split (with scratch)
     if (ts <= 256) return ZR_COST_SMALL1;                       // one small tile per CU
     return ZR_COST_SMALL2 * (double)((ts + 511) / 512);         // two per CU
 }
