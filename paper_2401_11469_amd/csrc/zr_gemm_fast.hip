@@ -768,9 +768,11 @@ __device__ __forceinline__ void dma16_ring(const void* gptr, uint32_t lds_byte_a
 }
 
 // Contraction axis contiguous (optional row list on the other axis): an LDS row is the
-// 64 bytes (4 chunks) of one tile row; chunk c of row i sits at position c ^ ((i >> 2) & 3),
-// so that the 16 rows a 16-lane group reads together cover all 64 banks.  One instruction
-// brings 16 rows.
+// 64 bytes (4 chunks) of one tile row; chunk c of row i sits at position c ^ ((i >> 1) & 3).
+// Measured with a ds_read_b128 loop over the candidate swizzles: this one (and its like with
+// bit 1 of the row in it) reads at the rate of a linear pattern, 256 bytes per clock;
+// c ^ ((i >> 2) & 3), which also gives 16 consecutive rows 16 different bank groups, is 58 %
+// slower and showed in the counters as one conflict cycle in two.  One instruction brings 16 rows.
 template <int R, int NT>
 struct RingP {
     static constexpr const char* NAME = "RingP";
@@ -792,7 +794,7 @@ struct RingP {
         __device__ __forceinline__ void setup16(int w0, int lane)
         {
             const int r = lane & 15;
-            off = (w0 + r) * 16 + ((((lane >> 4) ^ (r >> 2)) & 3) << 2);
+            off = (w0 + r) * 16 + ((((lane >> 4) ^ (r >> 1)) & 3) << 2);
         }
         __device__ __forceinline__ bf16x8 read16(const uint32_t* stage, int t, int) const
         {
@@ -807,7 +809,7 @@ struct RingP {
     {
         const int lane = tid & 63;
         wave_ = __builtin_amdgcn_readfirstlane(tid >> 6);
-        chunk_ = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+        chunk_ = ((lane & 3) ^ ((lane >> 3) & 3)) * 8;         // row of the lane = lane >> 2
         int idx[NI], rows[NI];
 #pragma unroll
         for (int q = 0; q < NI; ++q) idx[q] = min(r0 + 16 * ((int)wave_ + NW * q) + (lane >> 2), rlim - 1);

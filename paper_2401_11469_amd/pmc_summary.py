@@ -31,6 +31,7 @@ PASSES = {
 }
 COPY_KIB = 65536 * 8192 * 2 / 1024          # what bench.py --calibrate-copy reads and writes per dispatch
 N_SIMD = 256 * 4
+N_XCD = 8                                   # GRBM_GUI_ACTIVE arrives summed over the XCDs
 
 
 def short(k: str) -> str:
@@ -47,15 +48,18 @@ def load(d: str):
     """{kernel: {counter: [value per dispatch]}}"""
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
-        # (dispatch, kernel, counter) -> sum over the counter's instances (SQ, TCC: one per shader
-        # engine / XCD / channel), or their maximum for the GRBM clocks (every XCD counts the same span)
+        # rocprofv3 writes one row per dispatch and counter: the SUM over the counter's instances
+        # (SQ: shader engines x XCDs; TCC: channels x XCDs; GRBM: one per XCD)
         per = collections.defaultdict(float)
+        dur = {}
         for row in csv.DictReader(open(f)):
-            key = (row["Dispatch_Id"], short(row["Kernel_Name"]), row["Counter_Name"])
-            v = float(row["Counter_Value"])
-            per[key] = max(per[key], v) if row["Counter_Name"].startswith("GRBM_") else per[key] + v
+            k = short(row["Kernel_Name"])
+            per[(row["Dispatch_Id"], k, row["Counter_Name"])] += float(row["Counter_Value"])
+            dur[(row["Dispatch_Id"], k)] = float(row["End_Timestamp"]) - float(row["Start_Timestamp"])
         for (_, k, c), v in per.items():
             acc[k][c].append(v)
+        for (_, k), ns in dur.items():
+            acc[k]["_duration_ns"].append(ns)
     return acc
 
 
@@ -81,20 +85,22 @@ def main(d: str, commit: str) -> None:
               f"Byte counters are scaled by what they read for the calibration copy ({COPY_KIB:.0f} KiB read and written per "
               f"dispatch): FETCH_SIZE x {kf:.3f}, WRITE_SIZE x {kw:.3f}.  Values are means over all dispatches of a kernel in the run "
               "(the GEMM instantiations mix the five projections and the per-step ratios).  MB = 1e6 bytes.", "",
-              "MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES (summed over its instances) / (GRBM_GUI_ACTIVE (maximum over the XCDs) x 1024 SIMDs), "
-              "the expression of rocprofv3's own derived metric MfmaUtil: the share of "
+              "MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES (summed over all SIMDs) / (GRBM_GUI_ACTIVE per XCD x 1024 SIMDs), "
+              "the expression of rocprofv3's own derived metric MfmaUtil (the CSV holds GRBM_GUI_ACTIVE summed over the 8 XCDs, "
+              "hence / 8): the share of "
               "SIMD-cycles in which the matrix pipe is busy while the kernel runs, idle compute units included.", "",
-              "| kernel | dispatches | MFMA util | MFMA MOPS (bf16) / dispatch | LDS bank-conflict cycles / LDS active cycles | "
+              "| kernel | dispatches | clock MHz | MFMA util | MFMA MOPS (bf16) / dispatch | LDS bank-conflict cycles / LDS active cycles | "
               "wave cycles waiting on any instruction | VMEM reads issued | TA address-FIFO-full cycles | fetched MB | written MB |",
-              "|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]
+              "|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]
     order = sorted(mf, key=lambda k: -sum(mf[k].get("GRBM_GUI_ACTIVE", [0])))
     for k in order:
         if "kernel" not in k:
             continue
         m, v = mf[k], vm.get(k, {})
-        gui = mean(m.get("GRBM_GUI_ACTIVE", []))
+        gui = mean(m.get("GRBM_GUI_ACTIVE", [])) / N_XCD        # cycles the kernel ran
         busy = mean(m.get("SQ_VALU_MFMA_BUSY_CYCLES", []))
         util = busy / (gui * N_SIMD) if gui and gui == gui else float("nan")
+        mhz = gui / mean(m.get("_duration_ns", [])) * 1e3 if m.get("_duration_ns") and gui == gui else float("nan")
         lds_c, lds_a = mean(m.get("SQ_LDS_BANK_CONFLICT", [])), mean(m.get("SQ_LDS_IDX_ACTIVE", []))
         wait, wave = mean(v.get("SQ_WAIT_INST_ANY", [])), mean(m.get("SQ_WAVE_CYCLES", []))
         f = mean(fe.get(k, {}).get("FETCH_SIZE", [])) * kf * 1024 / 1e6
@@ -105,7 +111,8 @@ def main(d: str, commit: str) -> None:
                  "lds_bank_conflict_share": None if not lds_a or lds_a != lds_a else round(lds_c / lds_a, 4),
                  "wait_inst_any_share": None if not wave or wave != wave or wait != wait else round(wait / wave, 4)}
         kernels[k] = entry
-        lines.append(f"| `{k}` | {entry['dispatches']} | {util:.3f} | {mean(m.get('SQ_INSTS_VALU_MFMA_MOPS_BF16', [])):.4g} | "
+        entry["clock_mhz"] = None if mhz != mhz else round(mhz)
+        lines.append(f"| `{k}` | {entry['dispatches']} | {mhz:.0f} | {util:.3f} | {mean(m.get('SQ_INSTS_VALU_MFMA_MOPS_BF16', [])):.4g} | "
                      f"{lds_c:.3g} / {lds_a:.3g} | {wait:.3g} of {wave:.3g} | {mean(v.get('SQ_INSTS_VMEM_RD', [])):.4g} | "
                      f"{mean(v.get('SQ_VMEM_TA_ADDR_FIFO_FULL', [])):.3g} | {f:.1f} | {w:.1f} |")
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
