@@ -758,6 +758,12 @@ constexpr int RK = 32;
 #ifndef ZR_RING_LSLOT
 #define ZR_RING_LSLOT 2
 #endif
+#ifndef ZR_RING_ADIST
+#define ZR_RING_ADIST 2
+#endif
+#ifndef ZR_RING_LEARLY
+#define ZR_RING_LEARLY 0
+#endif
 
 __device__ __forceinline__ void dma16_ring(const void* gptr, uint32_t lds_byte_addr_uniform)
 {
@@ -913,7 +919,7 @@ __device__ __forceinline__ constexpr int ring_load(int gi, int b, int TM, int NL
 {
     if (b != ZR_RING_LSLOT) return -1;
     for (int j = 0; j < NLW; ++j)
-        if ((j * TM) / NLW == gi) return j;
+        if ((ZR_RING_LEARLY ? j : (j * TM) / NLW) == gi) return j;
     return -1;
 }
 
@@ -964,6 +970,7 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
     for (int b = 0; b < TN; ++b) bfr[0][b] = rb.read16(smem + A_WORDS, b, 0);
     afr[0] = ra.read16(smem, 0, 0);
     afr[1] = ra.read16(smem, 1, 0);
+    if (ZR_RING_ADIST == 3 && RA == 4) afr[2] = ra.read16(smem, 2, 0);
 
     // steady: the step is known to have a stage s + 3 to request (no branches around the loads)
     auto step = [&](int s, auto parity, auto steady) {
@@ -979,9 +986,10 @@ __device__ __forceinline__ void ring_main(LA& la, LB& lb, const typename LA::Rea
                 acc[gi][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[gi % RA], bfr[P][b], acc[gi][b], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (b == 0) {
-                    // row group gi + 2 of this stage, or of the next one (visible since the last
+                    // row group gi + AD of this stage, or of the next one (visible since the last
                     // barrier; after the last stage this reads stale LDS that nothing uses)
-                    afr[(gi + 2) % RA] = gi + 2 < TM ? ra.read16(rd, gi + 2, 0) : ra.read16(nx, gi + 2 - TM, 0);
+                    constexpr int AD = (ZR_RING_ADIST == 3 && RA == 4) ? 3 : 2;
+                    afr[(gi + AD) % RA] = gi + AD < TM ? ra.read16(rd, gi + AD, 0) : ra.read16(nx, gi + AD - TM, 0);
                 }
                 const int jb = ring_b_read(gi, b, TM, TN);
                 if (jb >= 0) bfr[P ^ 1][jb] = rb.read16(nx + A_WORDS, jb, 0);
