@@ -138,12 +138,23 @@ int zr_resize_select_multi(int32_t count, const float* const* scores, const int3
  * [M x n_keep rounded up to 64] bf16, zero padded, and then run the products on
  * ordinary loads.  The weight shard is never copied or compacted, in either
  * layout.  Without it (NULL, or too small) every gather is done in flight by
- * the GEMM loaders; results are the same to the last bit either way.
- * The tail of the buffer (both dtypes) serves ZR_IMPUTE_AVERAGE: the products'
- * epilogues leave per-tile sums of the stored results there, from which the means
- * of the dropped slices are taken; without it a second pass re-reads the kept
- * slices (means equal up to fp32 summation order).  Pure host function;
- * returns 0 on bad sizes. */
+ * the GEMM loaders.
+ * Layout: the extracted activation (bf16 only); then 64 MiB (bf16 only) for
+ * the slices of a split contraction; then, at the tail (both dtypes), the
+ * per-tile sums of ZR_IMPUTE_AVERAGE: the products' epilogues leave sums of
+ * the stored results there, from which the means of the dropped slices are
+ * taken; without it a second pass re-reads the kept slices (means equal up to
+ * fp32 summation order).
+ * Split contraction: a bf16 product (or remainder panel of one) that would
+ * occupy fewer than half of the chip's compute units and whose contraction is
+ * at least 1024 long is computed in 2..8 slices of the contraction in a first
+ * launch (fp32 partial results in the buffer) and summed, slice after slice,
+ * and stored by a second one.  Such a result differs from the one-launch result
+ * by fp32 summation order (the element-wise bound of the output type still
+ * holds); it is repeatable bit by bit for a given buffer size.  Results of
+ * products that are not split are the same to the last bit with and without
+ * the buffer.  A buffer smaller than this size is used as far as it reaches
+ * (extraction first).  Pure host function; returns 0 on bad sizes. */
 size_t zr_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t n_keep, int mode, int dtype);
 
 /* The extraction step on its own (Sec. 3.1, forward paragraph: the kept columns

@@ -1625,6 +1625,10 @@ int launch_inst(const FArgs& a, int i_base, int i_end, int j_base, int j_end, hi
     // Split contraction: when this launch has too few tiles for the chip and a long contraction,
     // s slices per tile (s * tiles workgroups), then one more launch of the same kernel that adds
     // the slices and runs the epilogue.  Needs scratch for the slices (the caller's workspace).
+    // (Tried on the big ring tiles of the dW products at high pruning ratios as well, 128 tiles
+    // of 192 x 256 in two slices each: the slices are 50 MB of fp32 that leave the chip at the
+    // end of the first launch and come back in the second, ~35 us per product, which is all
+    // that the better fill of the chip gains.  Not instantiated.)
     constexpr bool can_split = A::DMA && B::DMA && !ring && BM == 128 && BN == 128;
     if constexpr (can_split) {
         const int KT = (a.C + BK - 1) / BK;
