@@ -261,15 +261,21 @@ def main() -> int:
                "bytes": "rows x (n read + width written) x 2"}
 
     # ---- time vs ratio ---------------------------------------------------------
+    STEPS_PER_SAMPLE = 3
+
     def sample_steps(fn, n):
+        # a sample = STEPS_PER_SAMPLE steps enqueued back to back (as in the headline loop); with one
+        # step per sample the GPU waits for the host between the selection launch and the first
+        # product, 30-60 us that no pipelined caller sees
         ms = []
         for _ in range(n):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            fn()
+            for _ in range(STEPS_PER_SAMPLE):
+                fn()
             b.record()
             torch.cuda.synchronize()
-            ms.append(a.elapsed_time(b))
+            ms.append(a.elapsed_time(b) / STEPS_PER_SAMPLE)
         return np.array(ms)
 
     sweep = {}
@@ -286,7 +292,7 @@ def main() -> int:
                 base_ms = med
             fl = step_flops(r)
             sweep[f"{r:.2f}"] = {"ms": med, "p10": float(np.percentile(ms, 10)), "p90": float(np.percentile(ms, 90)),
-                                 "samples": args.samples, "ms_without_select": float(np.median(ms_nosel)),
+                                 "samples": args.samples, "steps_per_sample": STEPS_PER_SAMPLE, "ms_without_select": float(np.median(ms_nosel)),
                                  "tflops": fl / (med * 1e-3) / 1e12, "frac_peak": fl / (med * 1e-3) / 1e12 / peak,
                                  "speedup_vs_first": base_ms / med, "kept_fraction": fl / fl0,
                                  "linearity_residual": (med / base_ms) / (fl / fl0) - 1.0}

@@ -843,7 +843,7 @@ struct RingQT {
     static constexpr int NW = NT / 64;
     static constexpr int CPR = RP / 8;           // chunk slots per row
     static constexpr int RPI = 64 / CPR;         // rows per instruction
-    static constexpr bool FITS = (RK / RPI) % NW == 0 && R % 64 == 0 && R > RP / 2;
+    static constexpr bool FITS = (RK / RPI) % NW == 0 && R % 64 == 0 && R > RP / 2 && (RPI * NW) % 16 == 0;
     static constexpr int NI = FITS ? RK / RPI / NW : 1;
     static constexpr int SHORT = 0;
     __device__ __forceinline__ int count() const { return NI; }
