@@ -58,7 +58,7 @@ typedef enum {
     ZR_ERR_DTYPE = 5,
     ZR_ERR_MODE = 6,
     ZR_ERR_POLICY = 7,    /* unknown policy, or SAME without the previous tensor */
-    ZR_ERR_LIMIT = 8,     /* size beyond what the kernels index with int32 */
+    ZR_ERR_LIMIT = 8,     /* size beyond what the kernels index (M, K, N or rows above 65535 * 32; see each call) */
     ZR_ERR_HIP = 9        /* a HIP runtime call failed (launch error) */
 } zr_status;
 

@@ -9,6 +9,9 @@ using namespace zr;
 namespace {
 
 constexpr size_t kSplitScratchBytes = (size_t)64 << 20;
+// the fill kernels of the imputation passes put 32 rows on one workgroup of a grid's second dimension
+// (at most 65535 of them)
+constexpr int32_t kMaxRows = 65535 * 32;
 
 bool valid_dtype(int dt) { return dt == ZR_F32 || dt == ZR_BF16; }
 bool valid_mode(int m) { return m == ZR_DROP_N || m == ZR_DROP_K; }
@@ -21,6 +24,7 @@ int check_common(int32_t M, int32_t K, int32_t N, const int32_t* keep_idx, int32
     if (!valid_mode(mode)) return ZR_ERR_MODE;
     if (!valid_policy(policy)) return ZR_ERR_POLICY;
     if (M < 1 || K < 1 || N < 1) return ZR_ERR_SHAPE;
+    if (M > kMaxRows || K > kMaxRows || N > kMaxRows) return ZR_ERR_LIMIT;
     if (!keep_idx) return ZR_ERR_NULL;
     const int32_t n = mode == ZR_DROP_N ? N : K;
     if (n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
@@ -514,7 +518,7 @@ int zr_impute(void* out, int64_t ld, int32_t rows, int32_t cols, int32_t axis,
     const int32_t n = axis == 0 ? rows : cols;
     if (n_keep < 1 || n_keep > n) return ZR_ERR_INDEX;
     if (policy == ZR_IMPUTE_SAME && n_keep < n && !prev) return ZR_ERR_POLICY;
-    if (rows > (1 << 21)) return ZR_ERR_LIMIT;
+    if (rows > kMaxRows) return ZR_ERR_LIMIT;
     return launch_impute(out, ld, rows, cols, axis, keep_idx, n_keep, policy, prev, dtype,
                          (hipStream_t)stream);
 }

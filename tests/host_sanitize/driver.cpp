@@ -148,6 +148,10 @@ int main()
     EXPECT(zr_impute(P, 8, 4, 8, 0, KI, 5, ZR_IMPUTE_ZERO, nullptr, ZR_BF16, nullptr) == ZR_ERR_INDEX);
     EXPECT(zr_impute(P, 8, 4, 8, 1, KI, 4, ZR_IMPUTE_SAME, nullptr, ZR_BF16, nullptr) == ZR_ERR_POLICY);
     EXPECT(zr_impute(P, 8, (1 << 21) + 1, 8, 1, KI, 4, ZR_IMPUTE_ZERO, nullptr, ZR_BF16, nullptr) == ZR_ERR_LIMIT);
+    // 32 rows per workgroup of a grid dimension that holds 65535: the last size that fits, and the first that does not
+    EXPECT(zr_impute(P, 8, 65535 * 32 + 1, 8, 1, KI, 4, ZR_IMPUTE_ZERO, nullptr, ZR_BF16, nullptr) == ZR_ERR_LIMIT);
+    EXPECT(zr_resized_linear_fwd(P, 8, P, 8, P, 8, 65535 * 32 + 1, 8, 8, KI, 4, ZR_DROP_K, ZR_W_KN, ZR_BF16, ZR_IMPUTE_ZERO,
+                                 nullptr, nullptr, 0, nullptr) == ZR_ERR_LIMIT);
     EXPECT(zr_impute(P, 8, 4, 8, 1, KI, 4, ZR_IMPUTE_AVERAGE, nullptr, ZR_F32, nullptr) == ZR_OK);
     EXPECT(zr_priority_scores(nullptr, P, 8, 4, 8, ZR_DROP_N, nullptr, nullptr, 0, SC, ZR_BF16, nullptr, 0, nullptr) == ZR_ERR_NULL);
     EXPECT(zr_priority_scores(P, P, 7, 4, 8, ZR_DROP_N, nullptr, nullptr, 0, SC, ZR_BF16, nullptr, 0, nullptr) == ZR_ERR_SHAPE);
