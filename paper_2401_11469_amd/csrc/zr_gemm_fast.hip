@@ -32,6 +32,7 @@
 #include <type_traits>
 
 #include "zr_common.h"
+#include <cstring>
 
 namespace zr {
 
@@ -1772,9 +1773,32 @@ inline Sched plan_tiles(int I, int J)
     return best;
 }
 
+// ZR_FORCE_TILES in the environment (read once): "256", "192x256" or "256x192" sends every product
+// of this path to one grid of that tile shape, whatever the schedule would choose: a test switch
+// (small and ragged shapes then run through the big-tile kernels).  0 = not set.
+inline int forced_tiles()
+{
+    static const int f = [] {
+        const char* e = getenv("ZR_FORCE_TILES");
+        if (!e) return 0;
+        if (!strcmp(e, "256")) return 1;
+        if (!strcmp(e, "192x256")) return 2;
+        if (!strcmp(e, "256x192")) return 3;
+        return 0;
+    }();
+    return f;
+}
+
 template <template <int, int> class LA, template <int, int> class LB>
 int launch_shape(const FArgs& a, hipStream_t stream)
 {
+    if (const int f = forced_tiles()) {
+        if constexpr (LA<256, 512>::DMA && LB<256, 512>::DMA) {
+            if (f == 2) return launch_tile<LA, LB, 192, 256, 2, 4>(a, 0, a.I, 0, a.J, stream);
+            if (f == 3) return launch_tile<LA, LB, 256, 192, 4, 2>(a, 0, a.I, 0, a.J, stream);
+        }
+        return launch_tile<LA, LB, 256, 256, ZR_BIG_WM, ZR_BIG_WN>(a, 0, a.I, 0, a.J, stream);
+    }
     const Sched sc = plan_tiles(a.I, a.J);
     if constexpr (LA<256, 512>::DMA && LB<256, 512>::DMA) {
         const int64_t tj = tiles_of(a.I, a.J, 256, 192), ti = tiles_of(a.I, a.J, 192, 256);
