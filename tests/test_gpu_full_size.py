@@ -414,3 +414,35 @@ def test_big_tile_migrated_accumulate(zr, oracle):
         rows = np.sort(g.choice(M, size=24, replace=False))
         want = oracle.migrated_accumulate(base[rows], A[rows], B, transposed)
         check_kept_np("accumulate rows", _np64(out[torch.from_numpy(rows).cuda()]), want, "bf16", C)
+
+
+def test_big_tile_row_list_too_long_for_lds(zr):
+    """A row list on the contraction axis with more entries than the ring loop keeps in LDS (6144):
+    the product stays on 256 x 256 tiles but runs the 64-deep loop, which looks the list up as it goes."""
+    import torch
+    torch.manual_seed(11)
+    M, K, N = 4096, 8192, 4096
+    X = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+    W = (torch.randn(K, N, device="cuda") * 0.02).to(torch.bfloat16)
+    keep = torch.sort(torch.randperm(K, device="cuda")[:zr.keep_count(K, 0.1)]).values.to(torch.int32)
+    assert keep.numel() > 6144
+    ws = torch.empty(zr.workspace_bytes(M, K, N, keep.numel(), DROP_K, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    Y = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+    zr.resized_linear_fwd(X, W, keep, DROP_K, Y=Y, workspace=ws, w_layout=0)
+    torch.cuda.synchronize()
+    assert zr.debug_last_kernel() == "fast_kernel<DmaP, DmaQM, 256, 256, 2, 4>", zr.debug_last_kernel()
+    mask = torch.zeros(K, dtype=torch.float32, device="cuda")
+    mask[keep.long()] = 1.0
+    torch.backends.cuda.matmul.allow_tf32 = False
+    ref = (X.float() * mask[None, :]) @ (W.float() * mask[:, None])
+    check_kept_torch("long row list Y", Y, ref, "bf16", keep.numel(), None)
+    # one more kept index than the ring loop's limit, and exactly the limit (which takes the ring loop)
+    for nk, name in ((6145, "fast_kernel<DmaP, DmaQM, 256, 256, 2, 4>"), (6144, "fast_kernel<RingP, RingQM, 256, 256, 2, 4>")):
+        kp = keep[:nk].contiguous()
+        zr.resized_linear_fwd(X, W, kp, DROP_K, Y=Y, workspace=ws, w_layout=0)
+        torch.cuda.synchronize()
+        assert zr.debug_last_kernel() == name, (nk, zr.debug_last_kernel())
+        mask.zero_()
+        mask[kp.long()] = 1.0
+        ref = (X.float() * mask[None, :]) @ (W.float() * mask[:, None])
+        check_kept_torch(f"row list of {nk}", Y, ref, "bf16", nk, None)
