@@ -78,10 +78,10 @@ def main(d: str, commit: str) -> None:
     lines = ["# Hardware counters per kernel: bench.py on the Llama-2-7B TP=4 layer shard (bf16), one MI355X", "",
              f"Recorded at commit {commit}.  Commands (GPU box, from /tmp with TMPDIR=/tmp; one counter set per run):", ""]
     for tag, ctrs in PASSES.items():
-        lines.append(f"    rocprofv3 --pmc {ctrs} --output-format csv -d gpurun_out/pmc/{tag} -- python3 bench.py {BENCH_ARGS}")
-    lines += ["    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc/fetch_copy -- python3 bench.py --calibrate-copy",
-              "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc/write_copy -- python3 bench.py --calibrate-copy",
-              "    python3 -m paper_2401_11469_amd.pmc_summary gpurun_out/pmc <commit>", "",
+        lines.append(f"    rocprofv3 --pmc {ctrs} --output-format csv -d <dir>/{tag} -- python3 bench.py {BENCH_ARGS}")
+    lines += ["    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir>/fetch_copy -- python3 bench.py --calibrate-copy",
+              "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir>/write_copy -- python3 bench.py --calibrate-copy",
+              "    python3 -m paper_2401_11469_amd.pmc_summary <dir> <commit>", "",
               f"Byte counters are scaled by what they read for the calibration copy ({COPY_KIB:.0f} KiB read and written per "
               f"dispatch): FETCH_SIZE x {kf:.3f}, WRITE_SIZE x {kw:.3f}.  Values are means over all dispatches of a kernel in the run "
               "(the GEMM instantiations mix the five projections and the per-step ratios).  MB = 1e6 bytes.", "",
@@ -89,6 +89,9 @@ def main(d: str, commit: str) -> None:
               "the expression of rocprofv3's own derived metric MfmaUtil (the CSV holds GRBM_GUI_ACTIVE summed over the 8 XCDs, "
               "hence / 8): the share of "
               "SIMD-cycles in which the matrix pipe is busy while the kernel runs, idle compute units included.", "",
+              "Clock = GRBM_GUI_ACTIVE per XCD / the dispatch's duration.  The counter window is a few microseconds longer than "
+              "the dispatch, so the figure is a few per cent high for kernels of 100 us and meaningless for those of 10-20 us "
+              "(they read above the 2.4 GHz the chip can run at).", "",
               "| kernel | dispatches | clock MHz | MFMA util | MFMA MOPS (bf16) / dispatch | LDS bank-conflict cycles / LDS active cycles | "
               "wave cycles waiting on any instruction | VMEM reads issued | TA address-FIFO-full cycles | fetched MB | written MB |",
               "|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]

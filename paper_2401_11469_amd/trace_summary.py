@@ -28,8 +28,8 @@ def main(d: str, bench_json: str, out_md: str, args: str) -> None:
     out = [f"# rocprofv3 kernel trace: bench.py {args}", "",
            f"Workload: {bench['config']['workload']}", "",
            "Command (GPU box, from /tmp with TMPDIR=/tmp):", "",
-           f"    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof -- python3 bench.py {args}",
-           f"    python3 -m paper_2401_11469_amd.trace_summary gpurun_out/prof gpurun_out/prof/bench.json {out_md} \"{args}\"", "",
+           f"    rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -- python3 bench.py {args} > <dir>/bench.json",
+           f"    python3 -m paper_2401_11469_amd.trace_summary <dir> <dir>/bench.json {out_md} \"{args}\"", "",
            "The run executes warm-up + timed steps + the per-kernel event pass (a step = one selection launch, then forward and "
            "backward of every projection at the step's seeded ratio), so every instantiation below mixes several shapes and ratios.", "",
            "| kernel | calls | total ms | avg us | % |", "|---|---:|---:|---:|---:|"]
