@@ -446,3 +446,54 @@ def test_big_tile_row_list_too_long_for_lds(zr):
         mask[kp.long()] = 1.0
         ref = (X.float() * mask[None, :]) @ (W.float() * mask[:, None])
         check_kept_torch(f"row list of {nk}", Y, ref, "bf16", nk, None)
+
+
+def test_full_size_step_in_a_captured_graph(zr):
+    """One layer step of the Llama-2-7B shard (big ring tiles, remainder panels, split contractions,
+    extraction reuse) captured once and replayed with new priorities each time; every replay, with
+    eager work and synchronisations in between, equals the same step run eagerly bit by bit."""
+    import torch
+    sh = _Shard(zr, 4, only=("qkv", "out", "down"))
+    ratio = 0.25
+    kb = [torch.empty(p["n"], dtype=torch.int32, device="cuda") for p in sh.projs]
+    db = [torch.empty(p["n"], dtype=torch.int32, device="cuda") for p in sh.projs]
+
+    def step():
+        keeps, _ = zr.resize_select_multi([p["scores"] for p in sh.projs],
+                                          [wl.ratio_for(sh.cfg, p["pr"], ratio) for p in sh.projs], keep_idx=kb, drop_idx=db)
+        for p, keep in zip(sh.projs, keeps):
+            pr = p["pr"]
+            zr.resized_linear_fwd(p["X"], p["Wdev"], keep, pr.mode, Y=p["Y"], workspace=sh.ws, w_layout=p["layout"])
+            zr.resized_linear_bwd(p["X"], p["Wdev"], p["dY"], keep, pr.mode, dX=p["dX"], dW=p["dW"], workspace=sh.ws,
+                                  w_layout=p["layout"], workspace_holds_forward=True)
+        return keeps
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        keeps = step()
+    g = np.random.Generator(np.random.PCG64(17))
+    for rep in range(3):
+        for p in sh.projs:
+            p["scores"].copy_(torch.from_numpy(g.random(p["n"]).astype(np.float32)).cuda())
+            for k in ("Y", "dX", "dW"):
+                p[k].fill_(7.0)
+        sh.ws.fill_(0x5a)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [[p[k].clone() for k in ("Y", "dX", "dW")] for p in sh.projs] + [[k.clone() for k in keeps]]
+        for p in sh.projs:
+            for k in ("Y", "dX", "dW"):
+                p[k].fill_(9.0)
+        sh.ws.fill_(0xa5)
+        step()
+        torch.cuda.synchronize()
+        want = [[p[k] for k in ("Y", "dX", "dW")] for p in sh.projs] + [list(keeps)]
+        for a, b in zip(got, want):
+            for x, y in zip(a, b):
+                assert torch.equal(x, y), rep
+        for p in sh.projs:
+            for k in ("Y", "dX", "dW"):
+                assert torch.isfinite(p[k].float()).all()
