@@ -384,6 +384,22 @@ def main() -> int:
                                  "frac_hbm_peak": 8.0 * nb * nn / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                  "bytes": "algorithmic: 4n read + 4n written per vector"}
         del sc, kb, db
+        # one long vector (2^24 scores, 64 MB): many workgroups with scratch against the single workgroup
+        nl = 1 << 24
+        sl = torch.randn(nl, dtype=torch.float32, device=dev)
+        kl = torch.empty(nl, dtype=torch.int32, device=dev)
+        dl = torch.empty(nl, dtype=torch.int32, device=dev)
+        wsl = torch.empty(zr.select_workspace_bytes(nl), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: zr.resize_select_ws(sl, 0.25, wsl, keep_idx=kl, drop_idx=dl), n=10)
+        ms1 = timed(lambda: zr.resize_select_ws(sl, 0.25, None, keep_idx=kl, drop_idx=dl), n=2)
+        aux["select_large_n"] = {"n": nl, "ms": ms, "GB/s": 8.0 * nl / (ms * 1e-3) / 1e9,
+                                 "frac_hbm_peak": 8.0 * nl / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "physical_GB/s": 28.0 * nl / (ms * 1e-3) / 1e9,
+                                 "physical_frac_hbm_peak": 28.0 * nl / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "single_workgroup_ms": ms1,
+                                 "bytes": "algorithmic: 4n read + 4n written; physical: the vector is read by six "
+                                          "launches (four histograms, count, write) and the lists are written once"}
+        del sl, kl, dl, wsl
         keep25, _ = zr.resize_select(p0["scores"], 0.25)
         buf = p0["Y"] if p0["mode"] == zr.DROP_N else p0["dX"]
         ncols = buf.shape[1]

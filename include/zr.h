@@ -120,6 +120,23 @@ int64_t zr_keep_count(int64_t n, double ratio);
 int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio,
                      int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, void* stream);
 
+/* The same selection for ONE long vector, spread over many workgroups (Alg. 1's
+ * top-L_pri select at lengths far beyond a layer shard's, e.g. one list over
+ * a whole model).  With a DEVICE scratch buffer of at least
+ * zr_select_workspace_bytes(n) bytes (4-byte aligned; 68 KB) and n >= 131072
+ * the vector is cut into slices of 4096 scores, one wavefront each: four
+ * histogram launches (one per key byte), a count, a scan of the per-slice
+ * counts and the ordered write, every launch reading the vector once; all
+ * counters are integers, so the lists are the same, bit for bit, as
+ * zr_resize_select's.  Shorter vectors, or a missing / too small buffer, take
+ * zr_resize_select's single workgroup.  The buffer's contents are undefined
+ * afterwards; calls that share one must be ordered on one stream.
+ * zr_select_workspace_bytes: pure host function, 0 for n below the threshold.
+ *  Errors: NULL, SHAPE (n < 1), RATIO, LIMIT (n > 2^24). */
+size_t zr_select_workspace_bytes(int32_t n);
+int zr_resize_select_ws(const float* scores, int32_t n, double ratio, int32_t* keep_idx, int32_t* drop_idx,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* The same selection for `count` (<= 16) independent score vectors of different
  * lengths in ONE launch, e.g. all projections of a layer shard at the start of
  * a step.  scores, n, ratio, keep_idx, drop_idx are HOST arrays of `count`

@@ -214,6 +214,26 @@ int zr_resize_select(const float* scores, int32_t n, int32_t batch, double ratio
     return launch_select(scores, n, batch, (int)n_keep, keep_idx, drop_idx, ld_idx, (hipStream_t)stream);
 }
 
+size_t zr_select_workspace_bytes(int32_t n)
+{
+    if (n < 1) return 0;
+    return n >= select_wide_min_n() ? select_wide_workspace_bytes() : 0;
+}
+
+int zr_resize_select_ws(const float* scores, int32_t n, double ratio, int32_t* keep_idx, int32_t* drop_idx,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!scores || !keep_idx) return ZR_ERR_NULL;
+    if (n < 1) return ZR_ERR_SHAPE;
+    if (n > (1 << 24)) return ZR_ERR_LIMIT;
+    const int64_t n_keep = zr_keep_count(n, ratio);
+    if (n_keep < 1) return ZR_ERR_RATIO;
+    const bool wide = n >= select_wide_min_n() && workspace && (uintptr_t)workspace % 4 == 0 &&
+                      workspace_bytes >= select_wide_workspace_bytes();
+    if (!wide) return launch_select(scores, n, 1, (int)n_keep, keep_idx, drop_idx, n, (hipStream_t)stream);
+    return launch_select_wide(scores, n, (int)n_keep, keep_idx, drop_idx, workspace, (hipStream_t)stream);
+}
+
 int zr_resize_select_multi(int32_t count, const float* const* scores, const int32_t* n, const double* ratio,
                            int32_t* const* keep_idx, int32_t* const* drop_idx, void* stream)
 {

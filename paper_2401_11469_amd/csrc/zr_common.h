@@ -105,6 +105,11 @@ int launch_gemm(const GemmDesc& d, hipStream_t stream);
 int launch_gemm_fast(const GemmDesc& d, hipStream_t stream);   // -1: not eligible
 int launch_select(const float* scores, int n, int batch, int n_keep,
                   int32_t* keep_idx, int32_t* drop_idx, int64_t ld_idx, hipStream_t stream);
+// one long vector on many workgroups, with caller scratch of select_wide_workspace_bytes()
+size_t select_wide_workspace_bytes();
+int select_wide_min_n();
+int launch_select_wide(const float* scores, int n, int n_keep, int32_t* keep_idx, int32_t* drop_idx,
+                       void* workspace, hipStream_t stream);
 constexpr int ZR_SELECT_MULTI_MAX = 16;
 struct SelectMulti {
     const float* scores[ZR_SELECT_MULTI_MAX];

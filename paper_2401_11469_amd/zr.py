@@ -72,6 +72,10 @@ _lib.zr_migration_range.argtypes = [_i32, _i32, _i32, _i64, ctypes.POINTER(_i64)
 _lib.zr_migration_range.restype = ctypes.c_int
 _lib.zr_migrated_accumulate.argtypes = [_vp, _i64, _vp, _i64, ctypes.c_int, _vp, _i64, _i32, _i32, _i32, ctypes.c_int, _vp]
 _lib.zr_migrated_accumulate.restype = ctypes.c_int
+_lib.zr_select_workspace_bytes.argtypes = [_i32]
+_lib.zr_select_workspace_bytes.restype = ctypes.c_size_t
+_lib.zr_resize_select_ws.argtypes = [_vp, _i32, _f64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.zr_resize_select_ws.restype = ctypes.c_int
 _lib.zr_resize_select_multi.argtypes = [_i32, ctypes.POINTER(_vp), ctypes.POINTER(_i32), ctypes.POINTER(_f64),
                                         ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]
 _lib.zr_resize_select_multi.restype = ctypes.c_int
@@ -168,6 +172,33 @@ def resize_select(scores: torch.Tensor, ratio: float, keep_idx: Optional[torch.T
         k = k[0]
         d = None if d is None else d[0]
     return k, d
+
+
+def select_workspace_bytes(n: int) -> int:
+    return int(_lib.zr_select_workspace_bytes(n))
+
+
+def resize_select_ws(scores: torch.Tensor, ratio: float, workspace: Optional[torch.Tensor],
+                     keep_idx: Optional[torch.Tensor] = None, drop_idx: Optional[torch.Tensor] = None,
+                     want_drop: bool = True, stream=None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """One fp32 vector [n] on the GPU, with a scratch buffer (select_workspace_bytes(n) bytes) that lets a
+    long vector be selected by many workgroups.  Returns (keep_idx[n'], drop_idx[n - n'])."""
+    if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous() or scores.dim() != 1:
+        raise ValueError("scores: need a contiguous 1-D fp32 GPU tensor")
+    n = scores.shape[0]
+    n_keep = keep_count(n, ratio)
+    if n_keep < 1:
+        raise ZrError(3)
+    if keep_idx is None:
+        keep_idx = torch.empty(n_keep, dtype=torch.int32, device=scores.device)
+    if drop_idx is None and want_drop:
+        drop_idx = torch.empty(max(n - n_keep, 1), dtype=torch.int32, device=scores.device)
+    for t, need in ((keep_idx, n_keep), (drop_idx, n - n_keep)):
+        if t is not None and (t.dtype != torch.int32 or t.dim() != 1 or not t.is_contiguous() or t.numel() < need):
+            raise ValueError("index buffers: contiguous int32 vectors of at least n' and n - n' entries")
+    _check(_lib.zr_resize_select_ws(scores.data_ptr(), n, float(ratio), keep_idx.data_ptr(),
+                                    None if drop_idx is None else drop_idx.data_ptr(), *_ws(workspace), _stream(stream)))
+    return keep_idx[:n_keep], None if drop_idx is None else drop_idx[:n - n_keep]
 
 
 def resize_select_multi(scores, ratios, keep_idx=None, drop_idx=None, stream=None):

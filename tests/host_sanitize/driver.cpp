@@ -59,6 +59,15 @@ int main()
     EXPECT(zr_resize_select(SC, 8, 1, 0.25, KI, KI, 5, nullptr) == ZR_ERR_SHAPE);        // ld < n'
     EXPECT(zr_resize_select(SC, 8, 1, 0.75, KI, KI, 5, nullptr) == ZR_ERR_SHAPE);        // ld < n - n'
     EXPECT(zr_resize_select(SC, 8, 3, 0.25, KI, nullptr, 6, nullptr) == ZR_OK);
+    // the many-workgroup form: same argument checks; a short vector, a missing or a small buffer take the single workgroup
+    EXPECT(zr_select_workspace_bytes(0) == 0 && zr_select_workspace_bytes(1000) == 0 && zr_select_workspace_bytes(1 << 20) > 0);
+    EXPECT(zr_resize_select_ws(nullptr, 8, 0.25, KI, KI, P, 1 << 20, nullptr) == ZR_ERR_NULL);
+    EXPECT(zr_resize_select_ws(SC, 0, 0.25, KI, KI, P, 1 << 20, nullptr) == ZR_ERR_SHAPE);
+    EXPECT(zr_resize_select_ws(SC, (1 << 24) + 1, 0.25, KI, KI, P, 1 << 20, nullptr) == ZR_ERR_LIMIT);
+    EXPECT(zr_resize_select_ws(SC, 8, 1.0, KI, KI, P, 1 << 20, nullptr) == ZR_ERR_RATIO);
+    EXPECT(zr_resize_select_ws(SC, 8, 0.25, KI, nullptr, nullptr, 0, nullptr) == ZR_OK);
+    EXPECT(zr_resize_select_ws(SC, 1 << 20, 0.25, KI, KI, P, 16, nullptr) == ZR_OK);
+    EXPECT(zr_resize_select_ws(SC, 1 << 20, 0.25, KI, KI, P, zr_select_workspace_bytes(1 << 20), nullptr) == ZR_OK);
     {
         const float* sc[17]; int32_t n[17]; double r[17]; int32_t* k[17]; int32_t* d[17];
         for (int b = 0; b < 17; ++b) { sc[b] = SC; n[b] = 16 + b; r[b] = 0.1 * (b % 5); k[b] = KI; d[b] = b % 2 ? KI : nullptr; }

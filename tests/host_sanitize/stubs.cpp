@@ -59,6 +59,14 @@ int launch_select(const float* s, int n, int batch, int n_keep, int32_t* k, int3
     require(s && k && n >= 1 && batch >= 1 && n_keep >= 1 && n_keep <= n && ld >= n_keep, "select arguments");
     return ZR_OK;
 }
+size_t select_wide_workspace_bytes() { return (1032 + 4 * 4096) * 4; }
+int select_wide_min_n() { return 131072; }
+int launch_select_wide(const float* s, int n, int n_keep, int32_t* k, int32_t*, void* ws, hipStream_t)
+{
+    ++g_launches;
+    require(s && k && ws && n >= select_wide_min_n() && n_keep >= 1 && n_keep <= n, "wide select arguments");
+    return ZR_OK;
+}
 int launch_select_multi(const SelectMulti& m, int count, hipStream_t)
 {
     ++g_launches;

@@ -79,6 +79,40 @@ def test_select_bit_exact(zr, torch_mod, oracle, n, kind):
         assert zr.keep_count(n, ratio) == oracle.keep_count(n, ratio)
 
 
+@pytest.mark.parametrize("n,ratio", [(131072, 0.25), (131073, 0.5), (200000, 0.05), (1 << 20, 0.3),
+                                     ((1 << 20) + 77, 0.0), (300001, 0.999), (1 << 22, 0.4)])
+@pytest.mark.parametrize("kind", ["normal", "ties", "special"])
+def test_select_on_many_workgroups_bit_exact(zr, torch_mod, oracle, n, ratio, kind):
+    """One long vector cut into slices of 16384 scores (with scratch): bit-exact against the oracle and
+    against the single-workgroup entry point; ties that straddle slices are resolved by index."""
+    torch = torch_mod
+    g = np.random.Generator(np.random.PCG64(n + int(ratio * 1000)))
+    if kind == "normal":
+        s = g.standard_normal(n).astype(np.float32)
+    elif kind == "ties":
+        s = g.integers(0, 5, size=n).astype(np.float32)           # a fifth of the vector ties with the threshold
+    else:
+        s = g.standard_normal(n).astype(np.float32)
+        idx = g.choice(n, size=n // 7, replace=False)
+        s[idx] = np.resize(np.array([np.nan, -0.0, 0.0, np.inf, -np.inf, 1.0, -1.0, 3e38, -3e38, 1e-45], np.float32), idx.size)
+    assert zr.select_workspace_bytes(n) > 0 and zr.select_workspace_bytes(131071) == 0
+    sg = torch.from_numpy(s).cuda()
+    ws = torch.full((zr.select_workspace_bytes(n),), 0xab, dtype=torch.uint8, device="cuda")
+    keep, drop = zr.resize_select_ws(sg, ratio, ws)
+    ok, od = oracle.resize_select(s, ratio)
+    assert np.array_equal(keep.cpu().numpy(), ok), (n, kind, ratio)
+    assert np.array_equal(drop.cpu().numpy(), od), (n, kind, ratio)
+    # again with the buffer as the first call left it, and without a drop list
+    keep2, none = zr.resize_select_ws(sg, ratio, ws, want_drop=False)
+    assert none is None and torch.equal(keep, keep2)
+    # the single workgroup: without scratch, and through the plain entry point
+    k1, d1 = zr.resize_select_ws(sg, ratio, None)
+    assert torch.equal(k1, keep) and torch.equal(d1, drop)
+    if n <= (1 << 20):
+        k0, d0 = zr.resize_select(sg, ratio)
+        assert torch.equal(k0, keep) and torch.equal(d0, drop)
+
+
 def test_select_special_values_and_batch(zr, torch_mod, oracle):
     torch = torch_mod
     s = np.array([np.nan, -0.0, 0.0, np.inf, -np.inf, 1.0, np.nan, 0.0, -1.0, 1.0, -np.nan, 3e38],
