@@ -181,6 +181,15 @@ def main() -> int:
             pr = p["pr"]
             full = keep.numel() == p["n"]
             fl = 2.0 * M * pr.K * pr.N * keep.numel() / p["n"]
+            # algorithmic bytes of a product: the kept operand slices read once, the full-shape output written once
+            esz = p["X"].element_size()
+            nk = keep.numel()
+            if p["mode"] == zr.DROP_K:
+                nbytes = {"fwd": M * nk + nk * pr.N + M * pr.N, "dX": M * pr.N + nk * pr.N + M * pr.K,
+                          "dW": M * nk + M * pr.N + pr.K * pr.N}
+            else:
+                nbytes = {"fwd": M * pr.K + pr.K * nk + M * pr.N, "dX": M * nk + pr.K * nk + M * pr.K,
+                          "dW": M * pr.K + M * nk + pr.K * pr.N}
             for op in ("fwd", "dX", "dW"):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(); e1.record()            # creates the HIP events
@@ -193,7 +202,7 @@ def main() -> int:
                 else:
                     zr.resized_linear_bwd(p["X"], p["W"], p["dY"], keep, p["mode"], dW=p["dW"], need_dX=False,
                                           workspace=ws, w_layout=p["layout"], workspace_holds_forward=True)
-                events.append((zr.debug_last_kernel(), fl, e0, e1))
+                events.append((zr.debug_last_kernel(), fl, e0, e1, float(esz * nbytes[op])))
             if ws is not None and not full and tdt == torch.bfloat16:
                 src = p["X"] if p["mode"] == zr.DROP_K else p["dY"]
                 width = (keep.numel() + 63) // 64 * 64
@@ -232,14 +241,18 @@ def main() -> int:
         run_step_events(r, events)
     torch.cuda.synchronize()
     per = {}
-    for label, fl, e0, e1 in events:
-        d = per.setdefault(label, [0, 0.0, 0.0])
+    for label, fl, e0, e1, nb in events:
+        d = per.setdefault(label, [0, 0.0, 0.0, 0.0])
         d[0] += 1
         d[1] += fl
         d[2] += e0.elapsed_time(e1)
+        d[3] += nb
     pmc = load_pmc()
     pmc_k = pmc.get("kernels", {}) if args.config == 4 else {}
+    # (algorithmic GB/s and FLOP per byte beside the TFLOP/s: a product below ~310 FLOP/B, such as the
+    # GPT-2 shard's `out` projection with a contraction of 256, is bound by HBM, not by the matrix pipes)
     kernels = {k: {"launches": v[0], "avg_ms": v[2] / v[0], "tflops": v[1] / (v[2] * 1e-3) / 1e12,
+                   "algorithmic_GB/s": v[3] / (v[2] * 1e-3) / 1e9, "flop_per_byte": v[1] / v[3],
                    "mfma_util": pmc_k.get(k, {}).get("mfma_util")} for k, v in per.items()}
     dom = max(per.items(), key=lambda kv: kv[1][2])
     dom_tflops = dom[1][1] / (dom[1][2] * 1e-3) / 1e12
