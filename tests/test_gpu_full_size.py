@@ -497,3 +497,64 @@ def test_full_size_step_in_a_captured_graph(zr):
         for p in sh.projs:
             for k in ("Y", "dX", "dW"):
                 assert torch.isfinite(p[k].float()).all()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_large_ragged_shapes(zr, seed):
+    """Shapes the workloads do not have: every extent ragged (multiples of 8 only), large enough for the
+    schedule to cut big-tile panels and remainder panels along rows or columns; forward, dX and dW of both
+    modes in the row-selecting layouts, with the scratch buffer; whole tensors element-wise against the
+    masked-dense identity (fp32 library GEMM), imputed positions exact."""
+    import torch
+    g = np.random.Generator(np.random.PCG64(4000 + seed))
+    M = int(g.integers(190, 800)) * 8
+    K = int(g.integers(150, 560)) * 8
+    N = int(g.integers(150, 560)) * 8
+    mode = DROP_N if seed % 2 == 0 else DROP_K
+    ratio = float(g.choice([0.05, 0.15, 0.25, 0.35, 0.5]))
+    n = N if mode == DROP_N else K
+    nk = mode == DROP_N                                   # column-parallel shards are stored [N x K]
+    torch.manual_seed(seed)
+    X = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+    W = (torch.randn(K, N, device="cuda") * 0.02).to(torch.bfloat16)
+    dY = torch.randn(M, N, device="cuda", dtype=torch.bfloat16)
+    Wdev = W.t().contiguous() if nk else W
+    keep = torch.sort(torch.randperm(n, device="cuda")[:zr.keep_count(n, ratio)]).values.to(torch.int32)
+    ws = torch.empty(zr.workspace_bytes(M, K, N, keep.numel(), mode, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    Y = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+    dX = torch.full((M, K), 3.0, device="cuda", dtype=torch.bfloat16)
+    dW = torch.full((N, K) if nk else (K, N), 3.0, device="cuda", dtype=torch.bfloat16)
+    kernels = []
+    zr.resized_linear_fwd(X, Wdev, keep, mode, Y=Y, workspace=ws, w_layout=1 if nk else 0)
+    kernels.append(zr.debug_last_kernel())
+    zr.resized_linear_bwd(X, Wdev, dY, keep, mode, dX=dX, need_dW=False, workspace=ws, w_layout=1 if nk else 0,
+                          workspace_holds_forward=True)
+    kernels.append(zr.debug_last_kernel())
+    zr.resized_linear_bwd(X, Wdev, dY, keep, mode, dW=dW, need_dX=False, workspace=ws, w_layout=1 if nk else 0,
+                          workspace_holds_forward=mode == DROP_K)
+    kernels.append(zr.debug_last_kernel())
+    torch.cuda.synchronize()
+    print(f"M={M} K={K} N={N} mode={mode} ratio={ratio}: {kernels}", flush=True)
+    mask = torch.zeros(n, dtype=torch.float32, device="cuda")
+    mask[keep.long()] = 1.0
+    keptb = mask > 0
+    Xf, Wf, dYf = X.float(), W.float(), dY.float()
+    torch.backends.cuda.matmul.allow_tf32 = False
+    dWkn = dW.t() if nk else dW
+    tag = f"seed {seed}"
+    if mode == DROP_K:
+        Xm, Wm = Xf * mask[None, :], Wf * mask[:, None]
+        checks = (("Y", Y, Xm @ Wm, None, keep.numel()),
+                  ("dX", dX, (dYf @ Wm.T) * mask[None, :], keptb[None, :], N),
+                  ("dW", dWkn, (Xm.T @ dYf) * mask[:, None], keptb[:, None], M))
+        zs = (dX[:, ~keptb], dWkn[~keptb, :])
+    else:
+        Wm, dYm = Wf * mask[None, :], dYf * mask[None, :]
+        checks = (("Y", Y, (Xf @ Wm) * mask[None, :], keptb[None, :], K),
+                  ("dX", dX, dYm @ Wm.T, None, keep.numel()),
+                  ("dW", dWkn, (Xf.T @ dYm) * mask[None, :], keptb[None, :], M))
+        zs = (Y[:, ~keptb], dWkn[:, ~keptb])
+    for name, got, ref, wh, C in checks:
+        check_kept_torch(f"{tag} {name}", got, ref, "bf16", C, wh)
+    for z in zs:
+        assert torch.all(z == 0) and not torch.any(torch.signbit(z)), tag
