@@ -558,3 +558,45 @@ def test_random_large_ragged_shapes(zr, seed):
         check_kept_torch(f"{tag} {name}", got, ref, "bf16", C, wh)
     for z in zs:
         assert torch.all(z == 0) and not torch.any(torch.signbit(z)), tag
+
+
+def test_tensors_of_more_than_2_31_elements(zr):
+    """Activations of 266240 x 8192 elements (2.18e9, 4.4 GB in bf16): every row offset of the loaders,
+    the extraction and the epilogues has to be computed in 64 bits.  Rows from both ends of Y and dX and
+    the whole dW against fp32 library products of the same (masked) operands."""
+    import torch
+    M, K, N = 266240, 8192, 256
+    assert M * K > 2 ** 31
+    torch.manual_seed(3)
+    X = torch.empty(M, K, device="cuda", dtype=torch.bfloat16).normal_()
+    W = (torch.randn(K, N, device="cuda") * 0.02).to(torch.bfloat16)
+    dY = torch.randn(M, N, device="cuda", dtype=torch.bfloat16)
+    keep = torch.sort(torch.randperm(K, device="cuda")[:zr.keep_count(K, 0.25)]).values.to(torch.int32)
+    ws = torch.empty(zr.workspace_bytes(M, K, N, keep.numel(), DROP_K, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    Y = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+    dX = torch.full((M, K), 3.0, device="cuda", dtype=torch.bfloat16)
+    dW = torch.full((K, N), 3.0, device="cuda", dtype=torch.bfloat16)
+    zr.resized_linear_fwd(X, W, keep, DROP_K, Y=Y, workspace=ws, w_layout=0)
+    k_fwd = zr.debug_last_kernel()
+    zr.resized_linear_bwd(X, W, dY, keep, DROP_K, dX=dX, dW=dW, workspace=ws, w_layout=0, workspace_holds_forward=True)
+    torch.cuda.synchronize()
+    print(k_fwd, "|", zr.debug_last_kernel(), flush=True)
+    kl = keep.long()
+    mask = torch.zeros(K, dtype=torch.float32, device="cuda")
+    mask[kl] = 1.0
+    keptb = mask > 0
+    torch.backends.cuda.matmul.allow_tf32 = False
+    Wm = W.float() * mask[:, None]
+    rows = torch.cat([torch.arange(0, 300, device="cuda"), torch.arange(M // 2 - 150, M // 2 + 150, device="cuda"),
+                      torch.arange(M - 300, M, device="cuda")])
+    Xr, dYr = X[rows].float(), dY[rows].float()
+    check_kept_torch("Y rows", Y[rows], (Xr * mask[None, :]) @ Wm, "bf16", keep.numel(), None)
+    check_kept_torch("dX rows", dX[rows], (dYr @ Wm.T) * mask[None, :], "bf16", N, keptb[None, :])
+    assert torch.all(dX[rows][:, ~keptb] == 0)
+    # dW = X[:,S]^T dY over all tokens, accumulated in fp32 in chunks of rows
+    ref = torch.zeros(K, N, dtype=torch.float32, device="cuda")
+    for r0 in range(0, M, 32768):
+        ref += X[r0:r0 + 32768].float().T @ dY[r0:r0 + 32768].float()
+    ref *= mask[:, None]
+    check_kept_torch("dW", dW, ref, "bf16", M, keptb[:, None])
+    assert torch.all(dW[~keptb, :] == 0)
